@@ -75,40 +75,40 @@ def test_host_flow_matches_oracle_and_device_flow(gpu, oracle_mod):
     h.free()                                     # idempotent
 
 
-def test_big_random_config_sampled_rows_and_invariants(gpu, oracle_mod):
-    """Config 4 (20,000 states x 128,256 tokens, 2.6e9 pairs): the whole index is built on the GPU
-    in the benchmark's launch configuration; 48 rows are compared with the oracle entry by entry
-    and size-independent properties are checked on all of it."""
+def test_big_random_config_bit_exact(gpu, oracle_mod):
+    """Config 4's build (20,000 states x 128,256 tokens, 2.6e9 pairs, 2.2e8 entries), in the launch
+    configuration the benchmark times: row_ptr, token_ids and next_states against the oracle's,
+    element by element (in slices, so that one slice of each side is on the host at a time)."""
     import torch
     w = W.config_big_random()
     d, v = w.dfa, w.vocab
+    print("C4-big: oracle ...", flush=True)
+    ref = oracle_index(oracle_mod, d, v)
+    print(f"C4-big: oracle nnz={ref.nnz} W_bf={ref.w_bf}; GPU build ...", flush=True)
     prob = gpu.DeviceProblem(d.trans, d.byte_to_class, d.accept, d.dead, v.bytes, v.offsets, -1)
     csr, tok, nxt = prob.build()
     torch.cuda.synchronize()
     row_ptr = prob.row_ptr.cpu().numpy()
+    assert np.array_equal(row_ptr, ref.row_ptr), "C4-big: row_ptr differs"
     nnz = int(row_ptr[-1])
-    print(f"C4-big: nnz={nnz}", flush=True)
-    assert row_ptr[0] == 0 and (np.diff(row_ptr) >= 0).all() and nnz == tok.numel() > 2 ** 27
-    assert row_ptr[d.dead + 1] == row_ptr[d.dead]
-    # expected size under the generator: a walk of L bytes survives with probability 0.3^L
+    assert nnz == tok.numel() == nxt.numel() == ref.nnz > 2 ** 27
+    step = 1 << 25
+    for a in range(0, nnz, step):
+        b = min(a + step, nnz)
+        assert np.array_equal(tok[a:b].cpu().numpy(), ref.token_ids[a:b]), f"C4-big: token_ids differ in [{a}, {b})"
+        assert np.array_equal(nxt[a:b].cpu().numpy(), ref.next_states[a:b]), f"C4-big: next_states differ in [{a}, {b})"
+    # the one-call build into the same arrays gives the same bits
+    tok2 = torch.full_like(tok, -1)
+    nxt2 = torch.full_like(nxt, -1)
+    assert prob.build_into(tok2, nxt2) == nnz
+    torch.cuda.synchronize()
+    assert torch.equal(tok2, tok) and torch.equal(nxt2, nxt)
+    # properties that hold at any size
     lens = np.diff(v.offsets)
-    expect = 20000 * (0.3 ** lens).sum()
+    expect = 20000 * (0.3 ** lens).sum()         # a walk of L bytes survives with probability 0.3^L
     assert abs(nnz - expect) < 0.02 * expect
-    # ids ascend strictly inside every row; no entry ends in the dead state; all ids/states in range
-    starts = torch.zeros(nnz, dtype=torch.bool, device=tok.device)
-    rp = prob.row_ptr[:-1]
-    starts[rp[rp < nnz]] = True
-    asc = (tok[1:] > tok[:-1]) | starts[1:]
-    assert bool(asc.all())
-    assert int(tok.min()) >= 0 and int(tok.max()) < v.n_tokens
-    assert int(nxt.min()) >= 0 and int(nxt.max()) < d.n_states and not bool((nxt == d.dead).any())
-    ro = oracle_mod.RowOracle(d.trans, d.byte_to_class, d.accept, d.dead, v.bytes, v.offsets, -1)
-    rng = np.random.default_rng(4)
-    for q in [0, 1, d.dead - 1, d.dead] + rng.integers(0, d.n_states, size=44).tolist():
-        a, b = int(row_ptr[q]), int(row_ptr[q + 1])
-        rt, rn = ro.row(q)
-        assert np.array_equal(tok[a:b].cpu().numpy(), rt), q
-        assert np.array_equal(nxt[a:b].cpu().numpy(), rn), q
+    assert row_ptr[d.dead + 1] == row_ptr[d.dead]
+    assert not bool((nxt == d.dead).any())
 
 
 # ----------------------------------------------------------------------------- edge cases
@@ -293,6 +293,27 @@ def test_searched_segments_around_the_sizes_in_which_their_entries_leave(gpu, or
         assert int(ref.row_ptr[1]) >= n_first + 4096 + 600
         _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, eos)
         assert_same_index(ref, row_ptr, tok, nxt, f"n_first={n_first}, eos={eos}")
+
+
+@pytest.mark.parametrize("depth,eos,replicas", [(10, -1, 60), (12, 1, 60), (8, -1, 60), (3, 0, 200)])
+def test_emit_search_that_needs_more_frames_than_the_counting_walk(gpu, oracle_mod, depth, eos, replicas):
+    """Restricted to the admissible tokens the search of the emitting pass can hold more waiting
+    nodes than the counting walk did (see chain_case): the counting walk needs one frame on this
+    automaton, the emitting search one per level of the chain, more than it has for depth > 8; those
+    segments have to come out right all the same, in the two-call and in the one-call build."""
+    import torch
+    import chain_case
+    dfa, vocab = chain_case.chain_problem(depth, replicas)
+    ref = oracle_index(oracle_mod, dfa, vocab, eos)
+    assert int(np.diff(ref.row_ptr)[0]) > 512                      # state 0's segment is a searched one
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, eos)
+    assert_same_index(ref, row_ptr, tok, nxt, f"chain depth {depth}, two calls")
+    prob = gpu.DeviceProblem(dfa.trans, dfa.byte_to_class, dfa.accept, dfa.dead, vocab.bytes, vocab.offsets, eos)
+    tok = torch.full((ref.nnz,), -7, dtype=torch.int32, device="cuda")
+    nxt = torch.full((ref.nnz,), -7, dtype=torch.int32, device="cuda")
+    assert prob.build_into(tok, nxt) == ref.nnz
+    torch.cuda.synchronize()
+    assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok.cpu().numpy(), nxt.cpu().numpy(), f"chain depth {depth}, one call")
 
 
 def test_token_longer_than_32_bytes_with_a_chain_automaton(gpu, oracle_mod):

@@ -260,6 +260,52 @@ def test_walk_entry_point_matches_rows(oracle_mod):
             assert got == rows[q].get(t, -1)
 
 
+def test_row_entry_point_on_the_paper_examples_and_against_a_python_walk(oracle_mod):
+    """``oracle_index_row`` (one row at a time): the rows the paper's two worked examples fix, EOS
+    and dead rows, and a fold of delta written out here on a random automaton."""
+    for dfa, name in ((W.float_dfa(), "float_example.txt"), (W.name_dfa(), "name_example.txt")):
+        tokens, facts = read_golden(name)
+        vocab = W.Vocab.from_tokens(tokens)
+        tid = {t: i for i, t in enumerate(tokens)}
+        ro = oracle_mod.RowOracle(dfa.trans, dfa.byte_to_class, dfa.accept, dfa.dead, vocab.bytes, vocab.offsets, -1)
+        n_rows = 0
+        for f in facts:
+            if f[1] == "allowed":
+                assert sorted(ro.row(int(f[2]))[0].tolist()) == sorted(tid[t] for t in f[4:]), f
+            elif f[1] == "next":
+                got = dict(zip(*[a.tolist() for a in ro.row(int(f[2]))]))
+                assert got[tid[f[3]]] == int(f[5]), f
+            elif f[1] == "row":
+                want = [(tid[a], int(b)) for a, b in (p.rsplit(">", 1) for p in f[4:])]
+                assert list(zip(*[a.tolist() for a in ro.row(int(f[2]))])) == want, f
+                n_rows += 1
+        assert n_rows >= 3
+    rng = np.random.default_rng(77)
+    dfa = W.random_dfa(rng, 17, 6, 0.6)
+    vocab = W.bpe_like_vocab(rng, 400, 2.5, 7)
+    eos = 123
+    ro = oracle_mod.RowOracle(dfa.trans, dfa.byte_to_class, dfa.accept, dfa.dead, vocab.bytes, vocab.offsets, eos)
+    for q in range(dfa.n_states):
+        want = []
+        for t in range(vocab.n_tokens):
+            if q == dfa.dead:
+                break
+            if t == eos:
+                if dfa.accept[q]:
+                    want.append((t, q))
+                continue
+            s = q
+            for byte in vocab.token(t):
+                s = int(dfa.trans[s, dfa.byte_to_class[byte]])
+                if s == dfa.dead:
+                    break
+            if s != dfa.dead and len(vocab.token(t)) > 0:
+                want.append((t, s))
+        got = list(zip(*[a.tolist() for a in ro.row(q)])) if want else ro.row(q)[0].tolist()
+        assert got == want, q
+    assert ro.row(-1)[0].size == 0 and ro.row(dfa.n_states)[0].size == 0
+
+
 # ----------------------------------------------------------------------------- brute force
 
 TINY_REGEXES = [
