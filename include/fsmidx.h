@@ -235,6 +235,20 @@ int fsmidx_masked_argmax(const fsmidx_csr *index, const int32_t *states_dev, int
                          int32_t *tokens_out_dev, int32_t *states_out_dev, void *stream);
 
 /*
+ * masked_argmax without a workspace, for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and same results as fsmidx_masked_argmax; the partial results go to a fixed array of
+ * 2 MiB inside the library (one copy per GPU, held until the process ends), which limits a call
+ * to batch <= 4096: a larger batch is FSMIDX_INVALID_ARG.  The call allocates and frees nothing.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams
+ * or threads) race and give undefined results; calls on one stream are ordered and safe.  Nothing
+ * is carried over from one call to the next.  Asynchronous on `stream`.
+ */
+int fsmidx_masked_argmax_static(const fsmidx_csr *index, const int32_t *states_dev, int32_t batch,
+                                const void *logits, int64_t row_stride, int32_t dtype,
+                                int32_t *tokens_out_dev, int32_t *states_out_dev, void *stream);
+
+/*
  * masked_sample: the sampling step of Algorithm 2 (Section 2.2), s ~ Categorical(alpha~), with the
  * state update of Section 3.  On logits the masked distribution alpha~ is the softmax over the
  * tokens of row states[b]; the random number is the caller's: uniforms[b] in [0, 1).  The draw is

@@ -23,7 +23,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "fsmidx_index_csr",
            "fsmidx_index_to_host", "fsmidx_free_index", "fsmidx_build_workspace_bytes",
            "fsmidx_build_count", "fsmidx_build_fill", "fsmidx_build_into", "fsmidx_build_allow_bits", "fsmidx_mask_logits",
-           "fsmidx_advance_states", "fsmidx_masked_argmax_workspace_bytes", "fsmidx_masked_argmax",
+           "fsmidx_advance_states", "fsmidx_masked_argmax_workspace_bytes", "fsmidx_masked_argmax", "fsmidx_masked_argmax_static",
            "fsmidx_masked_sample_workspace_bytes", "fsmidx_masked_sample",
            "fsmidx_profile_enable", "fsmidx_profile_read")
 
@@ -93,6 +93,8 @@ def load():
     lib.fsmidx_masked_argmax_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
     lib.fsmidx_masked_argmax.argtypes = [POINTER(CCsr), c_void_p, c_int32, c_void_p, c_int64, c_int32, c_void_p,
                                          c_size_t, c_void_p, c_void_p, c_void_p]
+    lib.fsmidx_masked_argmax_static.argtypes = [POINTER(CCsr), c_void_p, c_int32, c_void_p, c_int64, c_int32, c_void_p,
+                                                c_void_p, c_void_p]
     lib.fsmidx_masked_sample_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
     lib.fsmidx_masked_sample.argtypes = [POINTER(CCsr), c_void_p, c_int32, c_void_p, c_int64, c_int32, c_void_p,
                                          c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
@@ -350,6 +352,20 @@ def masked_argmax(csr: CCsr, states, logits, workspace=None, tokens_out=None, st
     _check(load().fsmidx_masked_argmax(byref(csr), _ptr(states), batch, _ptr(logits), int(row_stride), int(dtype),
                                        _ptr(workspace), int(workspace.numel()), _ptr(tokens_out), _ptr(states_out),
                                        _stream_handle(stream)))
+    return tokens_out, states_out
+
+
+def masked_argmax_static(csr: CCsr, states, logits, tokens_out, states_out, row_stride=None, dtype=None, stream=None):
+    """fsmidx_masked_argmax_static: masked_argmax with the library's own fixed scratch array
+    (batch <= 4096); the caller passes the output tensors, nothing is allocated."""
+    import torch
+    batch = int(states.shape[0])
+    if dtype is None:
+        dtype = {torch.float32: DTYPE_F32, torch.bfloat16: DTYPE_BF16}.get(logits.dtype, -1)
+    if row_stride is None:
+        row_stride = logits.stride(0) if logits.dim() == 2 else int(csr.n_tokens)
+    _check(load().fsmidx_masked_argmax_static(byref(csr), _ptr(states), batch, _ptr(logits), int(row_stride), int(dtype),
+                                              _ptr(tokens_out), _ptr(states_out), _stream_handle(stream)))
     return tokens_out, states_out
 
 

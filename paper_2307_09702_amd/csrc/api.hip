@@ -197,6 +197,46 @@ static hipError_t read_status(const char *ws, const Plan &p, hipStream_t stream,
     return e;
 }
 
+// What advance_states, masked_argmax and masked_sample need of an index.
+int check_rows(const fsmidx_csr *index)
+{
+    if (!index)
+        return fail(FSMIDX_INVALID_ARG, "index must not be NULL");
+    if (index->n_states < 1 || index->n_tokens < 0 || index->nnz < 0)
+        return fail(FSMIDX_INVALID_ARG, "index sizes are inconsistent");
+    if (!index->row_ptr)
+        return fail(FSMIDX_INVALID_ARG, "index.row_ptr must not be NULL");
+    if (index->nnz > 0 && (!index->token_ids || !index->next_states))
+        return fail(FSMIDX_INVALID_ARG, "index.token_ids and index.next_states must not be NULL when nnz > 0");
+    return FSMIDX_OK;
+}
+
+// The argument checks that both masked_argmax entry points share (everything but where the partial
+// results go); *partial_bytes = the size of those partial results.
+int check_argmax_call(const fsmidx_csr *index, const int32_t *states_dev, int32_t batch, const void *logits,
+                      int64_t row_stride, int32_t dtype, const int32_t *tokens_out_dev, const int32_t *states_out_dev,
+                      size_t *partial_bytes)
+{
+    if (int rc = check_rows(index))
+        return rc;
+    if (dtype != 0 && dtype != 1)
+        return fail(FSMIDX_UNSUPPORTED, "dtype %d is not supported (0 = binary32, 1 = bfloat16)", dtype);
+    if (batch < 0 || batch > kArgmaxMaxBatch)
+        return fail(FSMIDX_INVALID_ARG, "batch must be in [0, %d]", kArgmaxMaxBatch);
+    *partial_bytes = align256((size_t)batch * kArgmaxSplits * sizeof(uint64_t));
+    if (batch == 0)
+        return FSMIDX_OK;
+    if (!states_dev || !logits || !tokens_out_dev || !states_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "states, logits, tokens_out and states_out must not be NULL");
+    if (row_stride < index->n_tokens)
+        return fail(FSMIDX_INVALID_ARG, "row_stride (%lld) is smaller than n_tokens (%d)", (long long)row_stride,
+                    index->n_tokens);
+    const size_t elem = dtype == 0 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(logits) & (elem - 1))
+        return fail(FSMIDX_INVALID_ARG, "logits must be aligned to the element size");
+    return FSMIDX_OK;
+}
+
 }  // namespace fsmidx
 
 using namespace fsmidx;
@@ -608,20 +648,6 @@ int fsmidx_mask_logits(const fsmidx_csr *index, const int32_t *states_dev, int32
     return FSMIDX_OK;
 }
 
-// What advance_states and masked_argmax need of an index.
-static int check_rows(const fsmidx_csr *index)
-{
-    if (!index)
-        return fail(FSMIDX_INVALID_ARG, "index must not be NULL");
-    if (index->n_states < 1 || index->n_tokens < 0 || index->nnz < 0)
-        return fail(FSMIDX_INVALID_ARG, "index sizes are inconsistent");
-    if (!index->row_ptr)
-        return fail(FSMIDX_INVALID_ARG, "index.row_ptr must not be NULL");
-    if (index->nnz > 0 && (!index->token_ids || !index->next_states))
-        return fail(FSMIDX_INVALID_ARG, "index.token_ids and index.next_states must not be NULL when nnz > 0");
-    return FSMIDX_OK;
-}
-
 int fsmidx_advance_states(const fsmidx_csr *index, const int32_t *states_dev, const int32_t *tokens_dev,
                           int32_t batch, int32_t *states_out_dev, void *stream_v)
 {
@@ -654,27 +680,16 @@ int fsmidx_masked_argmax(const fsmidx_csr *index, const int32_t *states_dev, int
                          int64_t row_stride, int32_t dtype, void *workspace, size_t workspace_bytes,
                          int32_t *tokens_out_dev, int32_t *states_out_dev, void *stream_v)
 {
-    if (int rc = check_rows(index))
-        return rc;
-    if (dtype != 0 && dtype != 1)
-        return fail(FSMIDX_UNSUPPORTED, "dtype %d is not supported (0 = binary32, 1 = bfloat16)", dtype);
     size_t need = 0;
-    if (int rc = fsmidx_masked_argmax_workspace_bytes(batch, &need))
+    if (int rc = check_argmax_call(index, states_dev, batch, logits, row_stride, dtype, tokens_out_dev, states_out_dev,
+                                   &need))
         return rc;
     if (batch == 0)
         return FSMIDX_OK;
-    if (!states_dev || !logits || !tokens_out_dev || !states_out_dev)
-        return fail(FSMIDX_INVALID_ARG, "states, logits, tokens_out and states_out must not be NULL");
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 7))
         return fail(FSMIDX_INVALID_ARG, "workspace must be a device pointer aligned to 8 bytes");
     if (workspace_bytes < need)
         return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu are needed", workspace_bytes, need);
-    if (row_stride < index->n_tokens)
-        return fail(FSMIDX_INVALID_ARG, "row_stride (%lld) is smaller than n_tokens (%d)", (long long)row_stride,
-                    index->n_tokens);
-    const size_t elem = dtype == 0 ? 4 : 2;
-    if (reinterpret_cast<uintptr_t>(logits) & (elem - 1))
-        return fail(FSMIDX_INVALID_ARG, "logits must be aligned to the element size");
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     prof_mark(7 + dtype, 0, stream);
     FSMIDX_HIP(launch_argmax(*index, states_dev, batch, logits, row_stride, dtype, static_cast<uint64_t *>(workspace),

@@ -147,4 +147,10 @@ hipError_t launch_sample(const fsmidx_csr &csr, const int32_t *states, int32_t b
 
 int fail(int code, const char *fmt, ...);   // records the thread's last error, returns code
 
+// Argument checks shared by the entry points that read rows of an index (api.hip).
+int check_rows(const fsmidx_csr *index);
+int check_argmax_call(const fsmidx_csr *index, const int32_t *states_dev, int32_t batch, const void *logits,
+                      int64_t row_stride, int32_t dtype, const int32_t *tokens_out_dev, const int32_t *states_out_dev,
+                      size_t *partial_bytes);
+
 }  // namespace fsmidx
