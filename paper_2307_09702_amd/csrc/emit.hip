@@ -160,20 +160,18 @@ __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord 
     }
 }
 
-constexpr uint32_t kNoSegment = 0xFFFFFFFFu;
-
-// Searched segments: this workgroup's share of the list.  Returns kNoSegment when the list is used
-// up -- or earlier, with a segment (state << 12 | block) whose search ran out of stack frames: the
-// caller walks that one and calls again.
-__device__ __forceinline__ uint32_t emit_by_search(const EmitArgs &a, const uint64_t *__restrict__ allow,
-                                                   const StateRecord *__restrict__ srec,
-                                                   const uint32_t *__restrict__ pairs, const uint64_t *__restrict__ U,
-                                                   const uint64_t *__restrict__ E, const int lane, EmitShared *sh)
+// Searched segments: this workgroup's share of the list.
+template <typename TabE>
+__device__ __forceinline__ void emit_by_search(const EmitArgs &a, const uint64_t *__restrict__ allow,
+                                               const TokenRecord *__restrict__ tok, const uint8_t *__restrict__ cls,
+                                               const TabE *__restrict__ tab, const StateRecord *__restrict__ srec,
+                                               const uint32_t *__restrict__ pairs, const uint64_t *__restrict__ U,
+                                               const uint64_t *__restrict__ E, const int lane, EmitShared *sh)
 {
     uint32_t *node_state = sh->search.node_state;
     uint8_t *node_of = sh->search.node_of;
     if (!a.st->use_sets)
-        return kNoSegment;
+        return;
     const uint32_t n_items = a.st->n_long;
     const uint32_t ch = (uint32_t)a.n_chunks;
     // Segments differ a lot in cost, so the waves take them one by one.  Atomics on one address
@@ -268,11 +266,30 @@ __device__ __forceinline__ uint32_t emit_by_search(const EmitArgs &a, const uint
                             }
                         });
         if (!searched) {
-            // Out of frames: the segment is walked token by token instead, like the short ones (the
-            // walk needs no stack; entries that nodes have stored directly are written again with
-            // the same values).
+            // Out of frames (rare): every lane walks the tokens of its own word one after the other
+            // through the table, which needs no stack.  Slow, but short and small; entries that nodes
+            // have stored directly are written again with the same values.  (EOS and empty tokens
+            // have length 0: the end state is the state itself.)
+            uint64_t rest = A;
+            int64_t at = base + first;
+            while (rest != 0) {
+                const int bit = __builtin_ctzll(rest);
+                rest &= rest - 1;
+                const int32_t t = b * kBlockTokens + lane * kChunkTokens + bit;
+                const TokenRecord rec = tok[t];
+                const uint64_t pk = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+                uint32_t s = (uint32_t)q;
+                for (uint32_t i = 0; i < rec.length; ++i) {
+                    const uint32_t c = i < (uint32_t)kPackedClasses ? (uint32_t)(pk >> (8 * i)) & 255u
+                                                                    : (uint32_t)cls[rec.offset + i];
+                    s = (uint32_t)tab[s * (uint32_t)a.n_classes + c];
+                }
+                a.token_ids[at] = t;
+                a.next_states[at] = (int32_t)s;
+                ++at;
+            }
             __builtin_amdgcn_wave_barrier();
-            return packed;
+            continue;
         }
         // (numbers are below n_nodes)
         const int planes =
@@ -415,27 +432,22 @@ __device__ __forceinline__ uint32_t emit_by_search(const EmitArgs &a, const uint
         }
         __builtin_amdgcn_wave_barrier();
     }
-    return kNoSegment;
 }
 
-// Row q, blocks [b0, b0 + n_here), n_here <= kWalkBlocks: the segments of these blocks that are
-// walked (all of them if searched_too, else all but the ones the searching workgroups take) as one
-// span of ranks.
+// Row q, blocks [b0, b0 + kWalkBlocks): the segments of these blocks that are walked (all but the
+// searched ones) as one span of ranks.
 template <typename E>
 __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__restrict__ allow,
                                           const TokenRecord *__restrict__ tok,
                                           const uint8_t *__restrict__ cls, const E *__restrict__ tab,
-                                          const int32_t q, const int32_t b0, const int n_here,
-                                          const bool searched_too, const uint32_t part,
+                                          const int32_t q, const int32_t b0, const uint32_t part,
                                           const uint32_t parts, const int lane, uint16_t *list)
 {
     uint64_t A[kWalkBlocks];
     uint32_t own[kWalkBlocks], first[kWalkBlocks], n_w[kWalkBlocks];
 #pragma unroll
     for (int w = 0; w < kWalkBlocks; ++w) {
-        A[w] = w < n_here && b0 + w < a.n_blocks
-                   ? allow[(int64_t)q * a.n_chunks + (int64_t)(b0 + w) * kBlockChunks + lane]
-                   : 0ull;
+        A[w] = b0 + w < a.n_blocks ? allow[(int64_t)q * a.n_chunks + (int64_t)(b0 + w) * kBlockChunks + lane] : 0ull;
         own[w] = (uint32_t)__popcll(A[w]);
     }
     // prefix sums over the lanes, two blocks per scan (a block has at most 4096 entries)
@@ -465,7 +477,7 @@ __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__r
     const int64_t row = a.row_ptr[q];
 #pragma unroll
     for (int w = 0; w < kWalkBlocks; ++w) {
-        if (per_block && !searched_too && n_w[w] > (uint32_t)kLongRow) {   // emitted by search
+        if (per_block && n_w[w] > (uint32_t)kLongRow) {             // emitted by search
             n_w[w] = 0;
             A[w] = 0;
             own[w] = 0;
@@ -543,46 +555,26 @@ __global__ __launch_bounds__(kWave) void emit_csr(const EmitArgs a, const uint64
                                                   const uint64_t *__restrict__ Ebits)
 {
     __shared__ EmitShared shared;
+    const int lane = threadIdx.x;
     // nothing to emit from a counting pass that has to be redone or was refused, and nothing if
     // the entries do not fit (uniform over the grid)
     if (a.st->overflow != 0 || a.st->flags != 0 || a.st->nnz > a.capacity)
         return;
-    // One loop for both kinds of workgroup, so that the walking code exists once: a searching
-    // workgroup comes through it only with a segment whose search ran out of stack.
-    const bool searching = blockIdx.x < a.n_long_groups;
+    if (blockIdx.x < a.n_long_groups) {
+        emit_by_search<E>(a, allow, tok, cls, tab, srec, pairs, U, Ebits, lane, &shared);
+        return;
+    }
     const uint32_t n_spans = ((uint32_t)a.n_blocks + kWalkBlocks - 1) / kWalkBlocks;
     const uint64_t n_items = (uint64_t)a.n_states * n_spans * a.parts;
-    uint64_t item = blockIdx.x - a.n_long_groups;
-    for (;;) {
-        // (the lane number taken afresh in every round: what either kind of work derives from it
-        // then stays inside that work instead of being kept in registers across the other kind)
-        int lane = threadIdx.x;
-        asm volatile("" : "+v"(lane));
-        int32_t q, b0;
-        int n_here = kWalkBlocks;
-        uint32_t part = 0, parts = 1;
-        if (searching) {
-            const uint32_t packed = emit_by_search(a, allow, srec, pairs, U, Ebits, lane, &shared);
-            if (packed == kNoSegment)
-                return;
-            q = (int32_t)(packed >> 12);
-            b0 = (int32_t)(packed & 0xFFFu);
-            n_here = 1;
-        } else {
-            if (item >= n_items)
-                return;
-            const uint64_t whole = item / a.parts;
-            part = (uint32_t)(item - whole * a.parts);
-            parts = a.parts;
-            const uint32_t slot = (uint32_t)(whole / n_spans);
-            const uint32_t span = (uint32_t)(whole - (uint64_t)slot * n_spans);
-            // token-set path: the states with several pairs first, as in the counting walk (their rows
-            // are the long ones, and what starts last is what the kernel ends with)
-            q = (int32_t)(a.st->use_sets != 0 ? a.order[slot] : slot);
-            b0 = (int32_t)(span * kWalkBlocks);
-            item += gridDim.x - a.n_long_groups;
-        }
-        emit_span<E>(a, allow, tok, cls, tab, q, b0, n_here, searching, part, parts, lane, shared.list);
+    for (uint64_t item = blockIdx.x - a.n_long_groups; item < n_items; item += gridDim.x - a.n_long_groups) {
+        const uint64_t whole = item / a.parts;
+        const uint32_t part = (uint32_t)(item - whole * a.parts);
+        const uint32_t slot = (uint32_t)(whole / n_spans);
+        const uint32_t span = (uint32_t)(whole - (uint64_t)slot * n_spans);
+        // token-set path: the states with several pairs first, as in the counting walk (their rows
+        // are the long ones, and what starts last is what the kernel ends with)
+        const uint32_t q = a.st->use_sets != 0 ? a.order[slot] : slot;
+        emit_span<E>(a, allow, tok, cls, tab, (int32_t)q, (int32_t)(span * kWalkBlocks), part, a.parts, lane, shared.list);
     }
 }
 
