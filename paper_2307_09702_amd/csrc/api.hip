@@ -75,6 +75,7 @@ int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_b
         return fail(FSMIDX_INVALID_ARG, "problem too large for one launch");
     size_t o = 0;
     p->off_status = o; o = align256(o + sizeof(Status));
+    p->off_sync = o;   o = align256(o + sizeof(SyncWords));
     p->off_cls = o;    o = align256(o + (size_t)n_bytes + 16);
     p->off_tok = o;    o = align256(o + (size_t)p->n_chunks * kChunkTokens * sizeof(TokenRecord));
     p->off_tab = o;    o = align256(o + (size_t)n_states * n_classes * p->entry_bytes + 16);
@@ -88,12 +89,12 @@ int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_b
     p->sets_possible = n_classes <= 64 && n_states <= 65535 && p->n_blocks > 0 && p->n_blocks <= kMaxSetBlocks;
     if (p->sets_possible) {
         const size_t max_pairs = (size_t)n_states * n_classes;
-        p->off_npairs = o;  o = align256(o + ((size_t)n_states + 1) * 4);
+        p->off_npairs = o;  o = align256(o + (size_t)n_states * 4);
         p->off_pmask = o;   o = align256(o + max_pairs * 8);
+        p->off_pslot = o;   o = align256(o + max_pairs * 4);
         p->off_pairs = o;   o = align256(o + max_pairs * 4 + 16);
         p->off_srec = o;    o = align256(o + (size_t)n_states * sizeof(StateRecord));
         p->off_order = o;   o = align256(o + (size_t)n_states * 4);
-        p->off_setmask = o; o = align256(o + (size_t)kSetCap * 8);
         p->off_clsets = o;  o = align256(o + (size_t)64 * (kSetCap / 64) * 8);
         p->off_U = o;       o = align256(o + (size_t)kMaxSetDepth * kSetCap * p->n_chunks * 8);
         p->off_E = o;       o = align256(o + (size_t)kMaxSetDepth * p->n_chunks * 8);
@@ -339,19 +340,61 @@ static int plan_for(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *work
     return FSMIDX_OK;
 }
 
-// Everything of the counting pass, enqueued.
+// Which counting kernel the device chose the last time this thread built an index from the same
+// inputs in the same workspace.  Only a hint for what to launch: the device decides afresh in every
+// build, and a launch sequence that left out the kernel it then wanted is noticed (Status::overflow
+// == 2) and the count is redone.  0 = unknown, 1 = token-set kernels, 2 = dense kernels.
+struct PathHint {
+    const void *ws = nullptr, *trans = nullptr, *bytes = nullptr;
+    int32_t n_states = 0, n_classes = 0, n_tokens = 0;
+    int path = 0;
+};
+constexpr int kPathHints = 8;
+static thread_local PathHint g_hints[kPathHints];
+static thread_local int g_next_hint = 0;
+
+static PathHint *find_hint(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, const char *ws, bool create)
+{
+    for (PathHint &h : g_hints)
+        if (h.ws == ws && h.trans == dfa->trans && h.bytes == vocab->bytes && h.n_states == dfa->n_states &&
+            h.n_classes == dfa->n_classes && h.n_tokens == vocab->n_tokens)
+            return &h;
+    if (!create)
+        return nullptr;
+    PathHint &h = g_hints[g_next_hint];
+    g_next_hint = (g_next_hint + 1) % kPathHints;
+    h.ws = ws;
+    h.trans = dfa->trans;
+    h.bytes = vocab->bytes;
+    h.n_states = dfa->n_states;
+    h.n_classes = dfa->n_classes;
+    h.n_tokens = vocab->n_tokens;
+    h.path = 0;
+    return &h;
+}
+
+static void remember_path(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, const char *ws, const Status &st)
+{
+    find_hint(dfa, vocab, ws, true)->path = (st.use_sets || st.feasible) ? 1 : 2;
+}
+
+// Everything of the counting pass, enqueued.  Without a hint both counting kernels are launched
+// and the one the device did not choose returns at once; with one, only the expected kernel.
 static int enqueue_count(const Plan &p, const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, char *ws,
                          int64_t *row_ptr_dev, hipStream_t stream)
 {
+    const PathHint *hint = find_hint(dfa, vocab, ws, false);
+    const int path = !p.sets_possible ? 2 : (hint ? hint->path : 0);
     prof_mark(0, 0, stream);
-    FSMIDX_HIP(launch_prepare(p, *dfa, *vocab, ws, stream));
-    if (p.sets_possible)
-        FSMIDX_HIP(launch_prepare_sets(p, *dfa, *vocab, ws, stream));
+    FSMIDX_HIP(launch_prepare(p, *dfa, *vocab, ws, path, stream));
+    if (path != 2)
+        FSMIDX_HIP(launch_token_sets(p, *dfa, *vocab, ws, stream));
     prof_mark(0, 1, stream);
     prof_mark(1, 0, stream);
-    if (p.sets_possible)
+    if (path != 2)
         FSMIDX_HIP(launch_walk_sets(p, *dfa, *vocab, ws, false, stream));
-    FSMIDX_HIP(launch_walk(p, *dfa, *vocab, ws, stream));
+    if (path != 1)
+        FSMIDX_HIP(launch_walk(p, *dfa, *vocab, ws, stream));
     prof_mark(1, 1, stream);
     prof_mark(2, 0, stream);
     FSMIDX_HIP(launch_scan(p, ws, row_ptr_dev, stream));
@@ -359,13 +402,15 @@ static int enqueue_count(const Plan &p, const fsmidx_dfa *dfa, const fsmidx_voca
     return FSMIDX_OK;
 }
 
-// A token-set walk needed more branch points than its stack holds: count again, the first time
-// with the deep stack, and if that overflows too (an automaton with deep branching) with the
-// workspace switched to the dense kernels.
+// The counting pass has to be redone.  A token-set walk needed more branch points than its stack
+// holds (overflow 1): the first time with the deep stack, and if that overflows too (an automaton
+// with deep branching) with the workspace switched to the dense kernels.  The device decided
+// against the token-set kernels and the dense one had not been launched (overflow 2): the dense
+// kernels at once.
 static int enqueue_recount(const Plan &p, const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, char *ws,
-                           int64_t *row_ptr_dev, int attempt, hipStream_t stream)
+                           int64_t *row_ptr_dev, int attempt, uint32_t why, hipStream_t stream)
 {
-    if (attempt == 0) {
+    if (attempt == 0 && why == 1) {
         FSMIDX_HIP(launch_retry_sets(p, ws, stream));
         FSMIDX_HIP(launch_walk_sets(p, *dfa, *vocab, ws, true, stream));
     } else {
@@ -406,11 +451,12 @@ int fsmidx_build_count(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *w
     if (st.flags)
         return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(st.flags), st.flags);
     for (int attempt = 0; st.overflow && attempt < 2; ++attempt) {
-        rc = enqueue_recount(p, dfa, vocab, ws, row_ptr_dev, attempt, stream);
+        rc = enqueue_recount(p, dfa, vocab, ws, row_ptr_dev, attempt, st.overflow, stream);
         if (rc)
             return rc;
         FSMIDX_HIP(read_status(ws, p, stream, &st));
     }
+    remember_path(dfa, vocab, ws, st);
     *nnz_host = st.nnz;
     return FSMIDX_OK;
 }
@@ -465,7 +511,7 @@ int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *wo
     if (st.flags)
         return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(st.flags), st.flags);
     for (int attempt = 0; st.overflow && attempt < 2; ++attempt) {
-        rc = enqueue_recount(p, dfa, vocab, ws, row_ptr_dev, attempt, stream);
+        rc = enqueue_recount(p, dfa, vocab, ws, row_ptr_dev, attempt, st.overflow, stream);
         if (rc)
             return rc;
         if (capacity > 0) {
@@ -475,6 +521,7 @@ int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *wo
         }
         FSMIDX_HIP(read_status(ws, p, stream, &st));
     }
+    remember_path(dfa, vocab, ws, st);
     *nnz_host = st.nnz;
     if (st.nnz > capacity)
         return fail(FSMIDX_OUTPUT_TOO_SMALL, "the index has %lld entries, the arrays hold %lld", (long long)st.nnz,

@@ -79,6 +79,7 @@ struct Plan {
     int32_t n_ranges = 0;          // ceil(n_states / states_per_wave)
     bool sets_possible = false;    // host-side necessary conditions for the token-set path
     size_t off_status = 0;         // Status
+    size_t off_sync = 0;           // SyncWords
     size_t off_cls = 0;            // uint8  [n_bytes]            class of every vocabulary byte
     size_t off_tok = 0;            // TokenRecord [n_chunks * 64]
     size_t off_tab = 0;            // uint16/uint32 [n_states * n_classes]
@@ -87,18 +88,23 @@ struct Plan {
     size_t off_rowtot = 0;         // int64  [n_states]
     size_t off_allow = 0;          // uint64 [n_states][n_chunks] admissibility bitmap
     // token-set path only
-    size_t off_npairs = 0;         // uint32 [n_states + 1]  pairs per state, then their starts
-    size_t off_pmask = 0;          // uint64 [n_states * n_classes] class set of each pair
-    size_t off_pairs = 0;          // uint32 [n_states * n_classes] target | set id << 16
+    size_t off_npairs = 0;         // uint32 [n_states]  pairs per state
+    size_t off_pmask = 0;          // uint64 [n_classes][n_states] class set of pair i of state q at i * n_states + q
+    size_t off_pslot = 0;          // uint32 [n_classes][n_states] its slot in the class-set table, same layout
+    size_t off_pairs = 0;          // uint32 [n_states][n_classes] target | set id << 16, state q's from q * n_classes
     size_t off_srec = 0;           // StateRecord [n_states]
     size_t off_order = 0;          // uint32 [n_states] the states, those with most pairs first
-    size_t off_setmask = 0;        // uint64 [kSetCap]
     size_t off_clsets = 0;         // uint64 [64][kSetCap / 64]  for every class, the sets that contain it
     size_t off_U = 0;              // uint64 [kMaxSetDepth][kSetCap][n_chunks]
     size_t off_E = 0;              // uint64 [kMaxSetDepth][n_chunks]
     size_t off_long = 0;           // uint32 [n_states * n_blocks] long segments: state << 12 | block
     size_t off_queue = 0;          // uint32 [256] work counters of the emit kernel
     size_t total = 0;
+};
+
+// What the numbering of the class sets leaves for the kernel that follows it.
+struct SyncWords {
+    uint32_t ids[kSetHashSlots];              // slot of the class-set table -> number of the set (0 .. n_sets - 1)
 };
 
 struct Status {       // mirrored at off_status
@@ -108,17 +114,22 @@ struct Status {       // mirrored at off_status
     uint32_t n_sets;       // distinct class sets
     uint32_t n_pairs;      // (state, target) pairs
     uint32_t long_tokens;  // some token is longer than kMaxSetDepth bytes
-    uint32_t overflow;     // a token-set walk ran out of stack frames: redo with the dense path
+    uint32_t overflow;     // the counting pass has to be redone: 1 = a token-set walk ran out of stack frames,
+                           // 2 = the host expected the token-set kernels to count, the device decided against them
     uint32_t n_long;       // length of the list of long (state, block) segments (token-set path)
+    uint32_t feasible;     // the token-set kernels could have counted, but the host had launched only the dense one
 };
 
 int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_bytes, Plan *plan);
 
 // Kernel launchers (each enqueues on `stream` and returns the launch error, if any).
-hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws,
+// expect: which counting kernel the host is going to launch: 0 = both (the device's choice runs,
+// the other returns at once), 1 = the token-set kernels only, 2 = the dense kernel only (see
+// Status::overflow and Status::feasible for what happens when the device would choose otherwise)
+hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws, int expect,
                           hipStream_t stream);
-hipError_t launch_prepare_sets(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws,
-                               hipStream_t stream);
+hipError_t launch_token_sets(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws,
+                             hipStream_t stream);
 // counting pass, either of two kernels (the choice is made on the device, see Status::use_sets)
 hipError_t launch_walk(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws, hipStream_t stream);
 hipError_t launch_walk_sets(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws, bool deep,

@@ -1,231 +1,42 @@
 // Preparation for the token-set walk (automata with at most 64 byte classes).
 //
-// The transition function delta (Section 3, Definition 1) is regrouped by target: state s gets a
-// list of pairs (target, class set), one per distinct non-rejecting target, smallest class set
-// first.  Class sets that occur anywhere in the automaton are numbered, and for every set S and
-// byte position d a bitmap over the vocabulary says which tokens are longer than d bytes and have
-// their d-th byte in S.  With these bitmaps "which tokens of this token set can state s read next"
-// -- the test inside Algorithm 3's inner loop, for a whole set of tokens at once -- is one AND.
+// The table narrowing kernel has regrouped the transition function delta (Section 3, Definition 1)
+// by target: state s has a list of pairs (target, class set), one per distinct non-rejecting
+// target, smallest class set first, and the class sets that occur anywhere in the automaton are
+// numbered.  Here, for every set S and byte position d, a bitmap over the vocabulary says which
+// tokens are longer than d bytes and have their d-th byte in S.  With these bitmaps "which tokens of
+// this token set can state s read next" -- the test inside Algorithm 3's inner loop, for a whole
+// set of tokens at once -- is one AND.
 //
-//  (the number of distinct targets per state comes from the table narrowing kernel)
-//  scan_u32    : their prefix sums
-//  pairs_fill  : the (target, class set) pairs, ordered by set size
-//  sets_dedupe : numbering of the distinct class sets; decides whether this path is taken
 //  token_sets  : bitmaps U[d][set][chunk] and the end-of-token bitmaps E[d][chunk]; also one
-//                16-byte record per state (pair count, first two pairs, start of the rest)
+//                16-byte record per state (pair count, first two pairs, start of the rest), the
+//                pairs' class sets renamed from table slots to set numbers on the way
 #include "internal.h"
 
 namespace fsmidx {
 
-// One wave per state; lane c holds the target of class c.  Calls f(k, target, class_mask) for the
-// k-th distinct live target in order of its lowest class; returns the number of targets.
-template <typename F>
-__device__ __forceinline__ int for_each_target(const uint16_t *__restrict__ tab, uint64_t live, int32_t q,
-                                               int32_t n_classes, int lane, F f)
+// The record of state q (the caller checks q < n_states).  The state's pairs start at q * n_classes
+// and hold their targets: here they get the numbers of their class sets (pslot: the sets' slots in
+// the table, pair i of state q at i * n_states + q; ids: slot -> number).
+__device__ __forceinline__ void state_record(const uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
+                                             const uint32_t *__restrict__ pslot, const uint32_t *__restrict__ ids,
+                                             int32_t n_states, int32_t n_classes, int32_t q,
+                                             StateRecord *__restrict__ srec)
 {
-    const uint32_t t = lane < n_classes ? tab[(int64_t)q * n_classes + lane] : 0u;
-    const bool is_live = (live >> lane) & 1ull;
-    uint64_t remaining = live;
-    int k = 0;
-    while (remaining) {
-        const int first = __builtin_ctzll(remaining);
-        const uint32_t tt = (uint32_t)__builtin_amdgcn_readlane((int)t, first);
-        const uint64_t grp = __ballot(is_live && t == tt);
-        remaining &= ~grp;
-        f(k, tt, grp);
-        ++k;
-    }
-    return k;
-}
-
-// Exclusive prefix sums of v[0..n) in place, v[n] = total (one workgroup); v = pairs per state.
-__global__ __launch_bounds__(1024) void scan_u32(uint32_t *__restrict__ v, int32_t n, uint32_t *total_out,
-                                                 uint32_t *__restrict__ order)
-{
-    __shared__ uint32_t wave_sum[16];
-    __shared__ uint32_t wave_many[16];
-    __shared__ uint32_t carry_s, carry_many_s;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) {
-        carry_s = 0;
-        carry_many_s = 0;
-    }
-    __syncthreads();
-    for (int32_t i0 = 0; i0 < n; i0 += 1024) {
-        const int32_t i = i0 + (int32_t)threadIdx.x;
-        const uint32_t x = i < n ? v[i] : 0u;
-        uint32_t incl = x;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t up = __shfl_up(incl, d, kWave);
-            if (lane >= d)
-                incl += up;
-        }
-        // The order in which the counting walk takes the states: those with two or more pairs
-        // first (ascending), the others after them (descending, filled from the end).  Searches
-        // from branching states are the long ones, and a long one that starts last is what the
-        // whole kernel then waits for.
-        const uint64_t many = __ballot(i < n && x >= 2u);
-        if (lane == kWave - 1) {
-            wave_sum[wave] = incl;
-            wave_many[wave] = (uint32_t)__popcll(many);
-        }
-        __syncthreads();
-        uint32_t before = carry_s, many_before = carry_many_s;
-        for (int w = 0; w < wave; ++w) {
-            before += wave_sum[w];
-            many_before += wave_many[w];
-        }
-        if (i < n) {
-            v[i] = before + incl - x;
-            const uint32_t rank = many_before + __builtin_amdgcn_mbcnt_hi((uint32_t)(many >> 32),
-                                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)many, 0u));
-            order[x >= 2u ? rank : (uint32_t)n - 1u - ((uint32_t)i - rank)] = (uint32_t)i;
-        }
-        __syncthreads();
-        if (threadIdx.x == 1023) {
-            carry_s = before + incl;
-            carry_many_s = many_before + (uint32_t)__popcll(many);
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        v[n] = carry_s;
-        *total_out = carry_s;
-    }
-}
-
-__global__ __launch_bounds__(256) void pairs_fill(const uint16_t *__restrict__ tab,
-                                                  const uint64_t *__restrict__ live, int32_t n_states,
-                                                  int32_t n_classes, const uint32_t *__restrict__ pbegin,
-                                                  uint64_t *__restrict__ pmask, uint32_t *__restrict__ pairs)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int32_t q = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (q >= n_states)
-        return;
-    uint32_t my_t = 0;
-    uint64_t my_m = 0;
-    const int n = for_each_target(tab, live[q], q, n_classes, lane, [&](int k, uint32_t tt, uint64_t grp) {
-        if (lane == k) {
-            my_t = tt;
-            my_m = grp;
-        }
-    });
-    // order: smaller class sets first (ties by lowest class), so the widest set -- typically the one
-    // that keeps a token set walking -- is last and can be followed without a stack frame
-    const uint32_t key = (uint32_t)__popcll(my_m) * 64u + (uint32_t)(my_m ? __builtin_ctzll(my_m) : 0);
-    uint32_t rank = 0;
-    for (int j = 0; j < n; ++j) {
-        const uint32_t kj = (uint32_t)__builtin_amdgcn_readlane((int)key, j);
-        rank += kj < key ? 1u : 0u;
-    }
-    if (lane < n) {
-        const uint32_t at = pbegin[q] + rank;
-        pmask[at] = my_m;
-        pairs[at] = my_t;
-    }
-}
-
-__device__ __forceinline__ uint32_t hash_mask(uint64_t m)
-{
-    m ^= m >> 29;
-    m *= 0x9E3779B97F4A7C15ull;
-    m ^= m >> 32;
-    return (uint32_t)m & (kSetHashSlots - 1);
-}
-
-// One workgroup.  Numbers the distinct class sets, rewrites every pair as target | set id << 16 and
-// takes the decision whether the token-set kernels run.
-__global__ __launch_bounds__(1024) void sets_dedupe(const uint64_t *__restrict__ pmask, uint32_t *__restrict__ pairs,
-                                                    uint64_t *__restrict__ setmask, uint64_t *__restrict__ class_sets,
-                                                    int32_t n_states, Status *st)
-{
-    __shared__ unsigned long long keys[kSetHashSlots];
-    __shared__ uint64_t by_id[kSetCap];
-    __shared__ uint32_t ids[kSetHashSlots];
-    __shared__ uint32_t wave_sum[16];
-    __shared__ uint32_t failed;
-    const uint32_t n_pairs = st->n_pairs;
-    for (int i = threadIdx.x; i < kSetHashSlots; i += blockDim.x)
-        keys[i] = 0ull;
-    if (threadIdx.x == 0)
-        failed = 0;
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < n_pairs; i += blockDim.x) {
-        const unsigned long long key = pmask[i];                 // never 0: a pair has at least one class
-        uint32_t h = hash_mask(key);
-        bool placed = false;
-        for (int probe = 0; probe < kSetHashSlots; ++probe) {
-            const unsigned long long old = atomicCAS(&keys[h], 0ull, key);
-            if (old == 0ull || old == key) {
-                placed = true;
-                break;
-            }
-            h = (h + 1) & (kSetHashSlots - 1);
-        }
-        if (!placed)
-            failed = 1;
-        pairs[i] = (pairs[i] & 0xFFFFu) | (h << 16);             // slot for now, id below
-    }
-    __syncthreads();
-    // compact the occupied slots into ids 0..n_sets-1
-    uint32_t n_sets = 0;
-    {
-        const int lane = threadIdx.x & (kWave - 1);
-        const int wave = threadIdx.x >> 6;
-        const bool occ = threadIdx.x < kSetHashSlots && keys[threadIdx.x] != 0ull;
-        const uint64_t b = __ballot(occ);
-        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
-        if (lane == 0)
-            wave_sum[wave] = (uint32_t)__popcll(b);
-        __syncthreads();
-        uint32_t before = 0;
-        for (int w = 0; w < 16; ++w) {
-            if (w < wave)
-                before += wave_sum[w];
-            n_sets += wave_sum[w];
-        }
-        if (occ) {
-            const uint32_t id = before + below;
-            ids[threadIdx.x] = id;
-            if (id < (uint32_t)kSetCap) {
-                setmask[id] = keys[threadIdx.x];
-                by_id[id] = keys[threadIdx.x];
-            }
-        }
-    }
-    __syncthreads();
-    const bool ok = failed == 0 && n_sets <= (uint32_t)kSetCap && n_pairs <= 3u * (uint32_t)n_states &&
-                    st->long_tokens == 0 && n_pairs < (1u << 24);
-    if (ok)
-        for (uint32_t i = threadIdx.x; i < n_pairs; i += blockDim.x)
-            pairs[i] = (pairs[i] & 0xFFFFu) | (ids[pairs[i] >> 16] << 16);
-    // the transpose: for every class, the sets that contain it (bit k of word k / 64 = set k)
-    if (ok && threadIdx.x < 64) {
-        uint64_t w[kSetCap / 64] = {};
-        for (uint32_t k = 0; k < n_sets; ++k)
-            if ((by_id[k] >> threadIdx.x) & 1ull)
-                w[k / 64] |= 1ull << (k & 63);
-        for (int j = 0; j < kSetCap / 64; ++j)
-            class_sets[threadIdx.x * (kSetCap / 64) + j] = w[j];
-    }
-    if (threadIdx.x == 0) {
-        st->n_sets = n_sets;
-        st->use_sets = ok ? 1u : 0u;
-    }
-}
-
-// The record of state q (the caller checks q < n_states).
-__device__ __forceinline__ void state_record(const uint32_t *__restrict__ pbegin, const uint32_t *__restrict__ pairs,
-                                             int32_t q, StateRecord *__restrict__ srec)
-{
-    const uint32_t b = pbegin[q], n = pbegin[q + 1] - b;
+    const uint32_t b = (uint32_t)q * (uint32_t)n_classes, n = npairs[q];
     StateRecord r;
     r.n_pairs = n;
-    r.pair0 = n > 0 ? pairs[b] : 0u;
-    r.pair1 = n > 1 ? pairs[b + 1] : 0u;
+    r.pair0 = 0u;
+    r.pair1 = 0u;
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t slot = pslot[(int64_t)i * n_states + q] & (uint32_t)(kSetHashSlots - 1);
+        const uint32_t named = (pairs[b + i] & 0xFFFFu) | ids[slot] << 16;
+        pairs[b + i] = named;
+        if (i == 0)
+            r.pair0 = named;
+        if (i == 1)
+            r.pair1 = named;
+    }
     r.ext = b + 2;
     srec[q] = r;
 }
@@ -262,9 +73,10 @@ constexpr int kSetChunks = 8;
 __global__ __launch_bounds__(kWave) void token_sets(const TokenRecord *__restrict__ tok, const uint8_t *__restrict__ cls,
                                                     const uint64_t *__restrict__ class_sets, int32_t n_chunks,
                                                     uint64_t *__restrict__ U, uint64_t *__restrict__ E,
-                                                    const uint32_t *__restrict__ pbegin,
-                                                    const uint32_t *__restrict__ pairs, int32_t n_states,
-                                                    StateRecord *__restrict__ srec, const Status *st)
+                                                    const uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
+                                                    const uint32_t *__restrict__ pslot,
+                                                    const uint32_t *__restrict__ ids, int32_t n_states,
+                                                    int32_t n_classes, StateRecord *__restrict__ srec, const Status *st)
 {
     static_assert(kBlockChunks % kSetChunks == 0, "n_chunks is a multiple of the group size");
     if (!st->use_sets)
@@ -275,7 +87,7 @@ __global__ __launch_bounds__(kWave) void token_sets(const TokenRecord *__restric
     if ((int32_t)blockIdx.x >= n_chunk_groups) {
         const int32_t q = ((int32_t)blockIdx.x - n_chunk_groups) * kWave + lane;
         if (blockIdx.y == 0 && q < n_states)
-            state_record(pbegin, pairs, q, srec);
+            state_record(npairs, pairs, pslot, ids, n_states, n_classes, q, srec);
         return;
     }
     const uint32_t d = blockIdx.y;
@@ -328,30 +140,22 @@ __global__ __launch_bounds__(kWave) void token_sets(const TokenRecord *__restric
     }
 }
 
-hipError_t launch_prepare_sets(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws,
-                               hipStream_t stream)
+hipError_t launch_token_sets(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws,
+                             hipStream_t stream)
 {
-    Status *st = reinterpret_cast<Status *>(ws + p.off_status);
-    const uint16_t *tab = reinterpret_cast<const uint16_t *>(ws + p.off_tab);
-    const uint64_t *live = reinterpret_cast<const uint64_t *>(ws + p.off_live);
-    uint32_t *npairs = reinterpret_cast<uint32_t *>(ws + p.off_npairs);
-    uint64_t *pmask = reinterpret_cast<uint64_t *>(ws + p.off_pmask);
-    uint32_t *pairs = reinterpret_cast<uint32_t *>(ws + p.off_pairs);
-    uint64_t *setmask = reinterpret_cast<uint64_t *>(ws + p.off_setmask);
-    StateRecord *srec = reinterpret_cast<StateRecord *>(ws + p.off_srec);
-    const dim3 per_state((p.n_states + 3) / 4);
-    hipLaunchKernelGGL(scan_u32, dim3(1), dim3(1024), 0, stream, npairs, p.n_states, &st->n_pairs,
-                       reinterpret_cast<uint32_t *>(ws + p.off_order));
-    hipLaunchKernelGGL(pairs_fill, per_state, dim3(256), 0, stream, tab, live, p.n_states, p.n_classes, npairs, pmask,
-                       pairs);
-    uint64_t *class_sets = reinterpret_cast<uint64_t *>(ws + p.off_clsets);
-    hipLaunchKernelGGL(sets_dedupe, dim3(1), dim3(1024), 0, stream, pmask, pairs, setmask, class_sets, p.n_states, st);
+    if (!p.sets_possible)
+        return hipSuccess;
+    const Status *st = reinterpret_cast<const Status *>(ws + p.off_status);
+    SyncWords *sy = reinterpret_cast<SyncWords *>(ws + p.off_sync);
     hipLaunchKernelGGL(token_sets, dim3(p.n_chunks / kSetChunks + (p.n_states + kWave - 1) / kWave, kMaxSetDepth),
-                       dim3(kWave), 0,
-                       stream, reinterpret_cast<const TokenRecord *>(ws + p.off_tok),
-                       reinterpret_cast<const uint8_t *>(ws + p.off_cls), class_sets, p.n_chunks,
-                       reinterpret_cast<uint64_t *>(ws + p.off_U), reinterpret_cast<uint64_t *>(ws + p.off_E), npairs, pairs,
-                       p.n_states, srec, st);
+                       dim3(kWave), 0, stream, reinterpret_cast<const TokenRecord *>(ws + p.off_tok),
+                       reinterpret_cast<const uint8_t *>(ws + p.off_cls),
+                       reinterpret_cast<const uint64_t *>(ws + p.off_clsets), p.n_chunks,
+                       reinterpret_cast<uint64_t *>(ws + p.off_U), reinterpret_cast<uint64_t *>(ws + p.off_E),
+                       reinterpret_cast<const uint32_t *>(ws + p.off_npairs),
+                       reinterpret_cast<uint32_t *>(ws + p.off_pairs),
+                       reinterpret_cast<const uint32_t *>(ws + p.off_pslot), sy->ids, p.n_states, p.n_classes,
+                       reinterpret_cast<StateRecord *>(ws + p.off_srec), st);
     return hipGetLastError();
 }
 

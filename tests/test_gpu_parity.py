@@ -431,6 +431,39 @@ def test_single_call_build_around_the_depths_of_both_search_stacks(gpu, oracle_m
     assert_same_index(ref, row_ptr, tok2, nxt2, f"longest={longest}, two calls")
 
 
+def test_builds_that_follow_a_hint_from_the_previous_build(gpu, oracle_mod):
+    """After a build the library remembers which counting kernel the device chose for these buffers
+    and launches only that one the next time.  Two automata of one shape, one for each kernel, are
+    written into the same device buffers in turn: a build that follows the wrong hint has to notice
+    and still give the right index, and the one after it follows the corrected hint."""
+    import torch
+    rng = np.random.default_rng(91)
+    chainy = few_target_dfa(rng, 120, 24, 2, 0.3)                     # token-set kernels
+    dense = W.random_dfa(rng, 120, 24, 0.7)                           # ~17 targets per state: dense kernel
+    assert chainy.n_states == dense.n_states and chainy.dead == dense.dead
+    dense = DFA(dense.trans, chainy.byte_to_class, dense.accept, dense.dead)
+    vocab = W.bpe_like_vocab(rng, 9000, 3.0, 12)
+    refs = {"chainy": oracle_index(oracle_mod, chainy, vocab, 5), "dense": oracle_index(oracle_mod, dense, vocab, 5)}
+    prob = gpu.DeviceProblem(chainy.trans, chainy.byte_to_class, chainy.accept, chainy.dead, vocab.bytes, vocab.offsets, 5)
+    cap = max(r.nnz for r in refs.values())
+    tok = torch.empty(cap, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(cap, dtype=torch.int32, device="cuda")
+    for step, name in enumerate(["chainy", "chainy", "dense", "dense", "dense", "chainy", "chainy", "chainy", "dense"]):
+        d = chainy if name == "chainy" else dense
+        prob.trans.copy_(torch.from_numpy(d.trans))
+        prob.accept.copy_(torch.from_numpy(d.accept))
+        torch.cuda.synchronize()
+        ref = refs[name]
+        if step % 2 == 0:
+            assert prob.build_into(tok, nxt) == ref.nnz
+        else:
+            assert prob.count() == ref.nnz
+            prob.fill(ref.nnz, tok, nxt)
+        torch.cuda.synchronize()
+        assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok[:ref.nnz].cpu().numpy(), nxt[:ref.nnz].cpu().numpy(),
+                          f"step {step}: {name}")
+
+
 def test_repeated_builds_are_identical(gpu):
     import torch
     w = W.config_json()
