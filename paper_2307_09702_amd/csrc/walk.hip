@@ -2,28 +2,37 @@
 // automata that the token-set walk does not take (many classes, many targets per state, long
 // tokens, more than 65535 states).
 //
-// Work decomposition.  A wave owns one token group (kChunksPerWave chunks of 64 tokens whose
-// records stay in registers for the whole kernel) and a range of consecutive states.  For each
-// state q of the range and each chunk, lane l decides the pair (q, token chunk*64 + l):
+// Work decomposition.  A workgroup of four waves owns one token group (1024 tokens, 16 chunks of
+// 64) and four ranges of consecutive states, one per wave.  The group's leading byte classes and
+// lengths are staged in LDS once per workgroup.  For each state q of its range a wave decides the
+// 1024 pairs (q, token):
 //
-//   step 0   the pair survives its first byte iff that byte's class is in the live-class mask of
-//            q (one bit test against a wave-uniform 64-bit mask -- Algorithm 3's "loop through
-//            states that read v_0" turned around: skip the states that do not);
-//   steps 1+ survivors follow the narrowed table until the token ends or the dead state is hit;
-//   ballot   the wave's admissibility word is the index as a bitmap; its popcount, summed over
-//            the group, is the length of the group's segment of row q.
+//   byte 0   row q of the narrowed table is put into LDS (one coalesced load), and every lane
+//            looks up its token's first class there: no memory gather at all.  This is Algorithm
+//            3's restriction to the states that can read the first symbol, turned around: for most
+//            automata most pairs end here.
+//   survivors (the walk goes on: not rejected, token longer than one byte) are compacted into a
+//            queue in LDS -- (state reached, token) -- so that the table lookups of the following
+//            bytes, which are gathers from memory, are issued by full waves however few pairs
+//            survive: a wave-wide gather costs the same whether one lane or all of them need it.
+//            The queue is compacted again after every byte, in place.
+//   finished pairs (token read to its end without meeting the dead state) set their bit in the
+//            wave's 1024-bit admissibility row in LDS; the row is the index as a bitmap, and its
+//            popcount is the length of the group's segment of row q.
 //
 // The end states are not kept: after the scans the emitting pass walks the admissible pairs again
-// and writes them in ascending token id.  No atomics are involved, so the CSR is deterministic.
+// and writes them in ascending token id.  Nothing here depends on the order in which atomics are
+// served (the only ones are ORs into the wave's own bitmap), so the CSR is deterministic.
 #include "internal.h"
 
 namespace fsmidx {
+
+constexpr int kWalkBatch = 4;          // gathers a lane has in flight when working off the queue
 
 struct WalkArgs {
     const TokenRecord *tok;
     const uint8_t *cls;
     const void *tab;
-    const uint64_t *live;
     const uint8_t *accept;
     uint32_t *cnt;             // [n_states][n_groups]
     int32_t n_states, n_classes, n_tokens, n_groups, n_ranges, states_per_wave;
@@ -34,41 +43,69 @@ struct WalkArgs {
     int32_t n_chunks;
 };
 
-// E: narrowed entry type.  TAB_LDS: the whole table is first copied to LDS.  USE_LIVE: n_classes
-// <= 64, so the live-class mask of a state is one 64-bit word.
-template <typename E, bool TAB_LDS, bool USE_LIVE>
+// LDS of one workgroup, after the table copy (TAB_LDS only).
+template <typename E>
+struct alignas(16) WalkShared {
+    uint64_t packed[kGroupTokens];                    // leading byte classes of the group's tokens, 8 bits each
+    uint16_t length[kGroupTokens];                    // their lengths (clamped to 65535: see the kernel)
+    struct PerWave {
+        E row[256];                                   // row q of the table
+        E state[kGroupTokens];                        // queue: state reached ...
+        uint16_t token[kGroupTokens];                 //        ... by this token of the group
+        uint64_t bits[kChunksPerWave];                // admissible tokens of the group from q
+    } wave[kWavesPerBlock];
+};
+
+// E: narrowed entry type.  TAB_LDS: the whole table is first copied to LDS.
+template <typename E, bool TAB_LDS>
 __global__ __launch_bounds__(kWave *kWavesPerBlock) void walk_pairs(const WalkArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     if (a.status->use_sets)
         return;                                                // uniform over the grid
     const E *tab = static_cast<const E *>(a.tab);
+    uint32_t tab_lds = 0;
     if (TAB_LDS) {
         const uint32_t n16 = a.tab_bytes / 16;                 // table bytes are padded to 16
         const uint4 *src = static_cast<const uint4 *>(a.tab);
         uint4 *dst = reinterpret_cast<uint4 *>(lds_raw);
         for (uint32_t i = threadIdx.x; i < n16; i += blockDim.x)
             dst[i] = src[i];
-        __syncthreads();
         tab = reinterpret_cast<const E *>(lds_raw);
+        tab_lds = a.tab_bytes;
     }
+    WalkShared<E> &sh = *reinterpret_cast<WalkShared<E> *>(lds_raw + tab_lds);
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    typename WalkShared<E>::PerWave &my = sh.wave[wave];
     const E dead_e = a.dead >= 0 ? (E)a.dead : (E) ~(E)0;
     const uint32_t n_classes = (uint32_t)a.n_classes;
-    // the grid is capped: a wave takes units blockIdx.x * 4 + wave, + 4 gridDim.x, ... (no barrier below)
-    const int64_t n_units = (int64_t)a.n_groups * a.n_ranges;
-    for (int64_t unit = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6); unit < n_units;
-         unit += (int64_t)gridDim.x * kWavesPerBlock) {
+    // the grid is capped: a workgroup takes units blockIdx.x, + gridDim.x, ...; a unit is one token
+    // group and kWavesPerBlock state ranges
+    const int32_t range_sets = (a.n_ranges + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t n_units = (int64_t)a.n_groups * range_sets;
+    for (int64_t unit = blockIdx.x; unit < n_units; unit += gridDim.x) {
         const int32_t g = (int32_t)(unit % a.n_groups);
-        const int32_t r = (int32_t)(unit / a.n_groups);
-        const int32_t q_lo = r * a.states_per_wave;
-        const int32_t q_hi = min(q_lo + a.states_per_wave, a.n_states);
+        const int32_t r = (int32_t)(unit / a.n_groups) * kWavesPerBlock + wave;
+        const int32_t q_lo = (int32_t)min((int64_t)r * a.states_per_wave, (int64_t)a.n_states);
+        const int32_t q_hi = (int32_t)min((int64_t)q_lo + a.states_per_wave, (int64_t)a.n_states);
         const int32_t t_base = g * kGroupTokens;
-
-        TokenRecord rec[kChunksPerWave];
+        __syncthreads();                                       // the last unit's tokens are no longer read (and, the
+                                                               // first time, the table copy is complete)
+        uint32_t first[kChunksPerWave];                        // per chunk, this lane's token: first class | length << 8
 #pragma unroll
-        for (int k = 0; k < kChunksPerWave; ++k)
-            rec[k] = a.tok[t_base + k * kWave + lane];
+        for (int k = 0; k < kChunksPerWave; ++k) {
+            const TokenRecord rec = a.tok[t_base + k * kWave + lane];
+            // (16 bits of length are enough here: they are only compared with the first eight byte
+            // positions; from the ninth byte on a walk reads the real length from the token's record)
+            const uint32_t len = min(rec.length, 65535u);
+            first[k] = (rec.cls_lo & 255u) | len << 8;
+            if (k % kWavesPerBlock == wave) {                  // every wave stages a quarter of the group
+                sh.packed[k * kWave + lane] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+                sh.length[k * kWave + lane] = (uint16_t)len;
+            }
+        }
+        __syncthreads();
         const bool group_has_eos = a.eos >= t_base && a.eos < t_base + kGroupTokens;
 
         for (int32_t q = q_lo; q < q_hi; ++q) {
@@ -79,60 +116,116 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void walk_pairs(const WalkAr
                     a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + lane] = 0;
                 continue;
             }
-            uint64_t live_q = 0;
-            if (USE_LIVE)
-                live_q = a.live[q];
-            const bool eos_here = group_has_eos && a.accept[q] != 0;
-            uint32_t count = 0;
+            // ---- byte 0 from row q in LDS
+            for (uint32_t c = (uint32_t)lane; c < n_classes; c += kWave)
+                my.row[c] = tab[(uint32_t)q * n_classes + c];
+            __builtin_amdgcn_wave_barrier();
+            uint32_t n = 0;                                        // pairs in the queue
 #pragma unroll
             for (int k = 0; k < kChunksPerWave; ++k) {
-                const uint32_t len = rec[k].length;
-                const uint64_t pk = ((uint64_t)rec[k].cls_hi << 32) | rec[k].cls_lo;
-                bool alive = len != 0;
-                if (USE_LIVE)
-                    alive = alive && ((live_q >> (pk & 63)) & 1);
-                uint32_t s = (uint32_t)q;
-                if (__any(alive)) {
-                    bool active = alive;
-                    uint32_t i = 0;
-                    while (__any(active)) {
-                        if (active) {
-                            uint32_t c;
-                            if (i < (uint32_t)kPackedClasses)
-                                c = (uint32_t)(pk >> (8 * i)) & 255u;
-                            else
-                                c = a.cls[rec[k].offset + i];
-                            s = tab[s * n_classes + c];
-                            if (s == (uint32_t)dead_e)
-                                alive = false;
-                        }
-                        ++i;
-                        active = alive && i < len;
-                    }
-                }
-                const int32_t t = t_base + k * kWave + lane;
-                if (eos_here && t == a.eos)
-                    alive = true;
-                const uint64_t word = __ballot(alive);
+                const uint32_t len = first[k] >> 8;
+                const E s1 = my.row[first[k] & 255u];
+                const bool alive = len != 0 && s1 != dead_e;
+                const uint64_t done = __ballot(alive && len == 1u);
+                const uint64_t more = __ballot(alive && len > 1u);
                 if (lane == 0)
-                    a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + k] = word;
-                count += (uint32_t)__popcll(word);
+                    my.bits[k] = done;
+                if (alive && len > 1u) {
+                    const uint32_t at = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(more >> 32),
+                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)more, 0u));
+                    my.state[at] = s1;
+                    my.token[at] = (uint16_t)(k * kWave + lane);
+                }
+                n += (uint32_t)__popcll(more);
             }
+            // EOS has no bytes: admissible exactly from accepting states
+            if (group_has_eos && a.accept[q] != 0 && lane == 0) {
+                const int32_t e = a.eos - t_base;
+                my.bits[e >> 6] |= 1ull << (e & 63);
+            }
+            __builtin_amdgcn_wave_barrier();
+            // ---- bytes 1, 2, ...: the queue, kWalkBatch * 64 pairs at a time, compacted in place
+            //      (a pair is written at or before the place it was read from, and the reads of a
+            //      batch are issued before its writes)
+            for (uint32_t d = 1; n != 0; ++d) {
+                uint32_t kept = 0;
+                for (uint32_t b0 = 0; b0 < n; b0 += kWalkBatch * kWave) {
+                    uint32_t s[kWalkBatch], t[kWalkBatch], c[kWalkBatch], len[kWalkBatch];
+                    E s2[kWalkBatch];
+                    bool valid[kWalkBatch];
+#pragma unroll
+                    for (int u = 0; u < kWalkBatch; ++u) {
+                        const uint32_t at = b0 + (uint32_t)(u * kWave + lane);
+                        valid[u] = at < n;
+                        s[u] = valid[u] ? (uint32_t)my.state[at] : 0u;
+                        t[u] = valid[u] ? (uint32_t)my.token[at] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kWalkBatch; ++u) {
+                        len[u] = sh.length[t[u]];
+                        if (d < (uint32_t)kPackedClasses) {
+                            c[u] = (uint32_t)(sh.packed[t[u]] >> (8 * d)) & 255u;
+                        } else {
+                            // (few walks get this far) the class string; a token of 65535 bytes or more has its
+                            // real length in its record
+                            c[u] = 0;
+                            if (valid[u]) {
+                                const TokenRecord rec = a.tok[t_base + (int32_t)t[u]];
+                                c[u] = a.cls[rec.offset + d];
+                                len[u] = rec.length;
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kWalkBatch; ++u)
+                        s2[u] = valid[u] ? tab[s[u] * n_classes + c[u]] : dead_e;
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int u = 0; u < kWalkBatch; ++u) {
+                        const bool alive = valid[u] && s2[u] != dead_e;
+                        const bool done = alive && len[u] == d + 1u;
+                        const bool more = alive && !done;
+                        if (done)
+                            atomicOr(reinterpret_cast<unsigned long long *>(&my.bits[t[u] >> 6]), 1ull << (t[u] & 63u));
+                        const uint64_t m = __ballot(more);
+                        if (more) {
+                            const uint32_t at = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                            my.state[at] = s2[u];
+                            my.token[at] = (uint16_t)t[u];
+                        }
+                        kept += (uint32_t)__popcll(m);
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+                n = kept;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // ---- the bitmap row of (q, group) and its popcount
+            uint32_t count = 0;
+            if (lane < kChunksPerWave) {
+                const uint64_t word = my.bits[lane];
+                a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + lane] = word;
+                count = (uint32_t)__popcll(word);
+            }
+#pragma unroll
+            for (int o = kChunksPerWave / 2; o >= 1; o >>= 1)
+                count += __shfl_xor(count, o, kWave);
             if (lane == 0)
                 a.cnt[(int64_t)q * a.n_groups + g] = count;
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
 
-template <typename E, bool TAB_LDS, bool USE_LIVE>
+template <typename E, bool TAB_LDS>
 static void launch_variant(const WalkArgs &a, int64_t n_units, size_t lds, hipStream_t stream)
 {
-    // at most 16 workgroups per compute unit: when the token-set kernel does the work instead,
-    // these have nothing to do but to find that out
-    const int64_t want = (n_units + kWavesPerBlock - 1) / kWavesPerBlock;
-    const dim3 grid((unsigned)(want < 4096 ? want : 4096));
+    // a few workgroups per compute unit: when the token-set kernel does the work instead, these have
+    // nothing to do but to find that out
+    const dim3 grid((unsigned)(n_units < 4096 ? n_units : 4096));
     const dim3 block(kWave * kWavesPerBlock);
-    hipLaunchKernelGGL((walk_pairs<E, TAB_LDS, USE_LIVE>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((walk_pairs<E, TAB_LDS>), grid, block, lds + sizeof(WalkShared<E>), stream, a);
 }
 
 hipError_t launch_walk(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws, hipStream_t stream)
@@ -143,7 +236,6 @@ hipError_t launch_walk(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab 
     a.tok = reinterpret_cast<const TokenRecord *>(ws + p.off_tok);
     a.cls = reinterpret_cast<const uint8_t *>(ws + p.off_cls);
     a.tab = ws + p.off_tab;
-    a.live = reinterpret_cast<const uint64_t *>(ws + p.off_live);
     a.accept = dfa.accept;
     a.cnt = reinterpret_cast<uint32_t *>(ws + p.off_cnt);
     a.n_states = p.n_states;
@@ -159,18 +251,14 @@ hipError_t launch_walk(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab 
     a.n_chunks = p.n_chunks;
     const size_t tab_bytes = ((size_t)p.n_states * p.n_classes * p.entry_bytes + 15) / 16 * 16;
     a.tab_bytes = (uint32_t)(tab_bytes <= 0xFFFFFFFFu ? tab_bytes : 0);
-    const int64_t n_units = (int64_t)p.n_groups * p.n_ranges;
-    const bool lds = tab_bytes <= 64 * 1024;
-    const bool use_live = p.n_classes <= 64;
+    const int64_t n_units = (int64_t)p.n_groups * ((p.n_ranges + kWavesPerBlock - 1) / kWavesPerBlock);
+    const bool lds = tab_bytes <= 32 * 1024;
     const size_t lds_bytes = lds ? tab_bytes : 0;
     if (p.entry_bytes == 2) {
-        if (lds && use_live) launch_variant<uint16_t, true, true>(a, n_units, lds_bytes, stream);
-        else if (lds) launch_variant<uint16_t, true, false>(a, n_units, lds_bytes, stream);
-        else if (use_live) launch_variant<uint16_t, false, true>(a, n_units, 0, stream);
-        else launch_variant<uint16_t, false, false>(a, n_units, 0, stream);
+        if (lds) launch_variant<uint16_t, true>(a, n_units, lds_bytes, stream);
+        else launch_variant<uint16_t, false>(a, n_units, 0, stream);
     } else {
-        if (use_live) launch_variant<uint32_t, false, true>(a, n_units, 0, stream);
-        else launch_variant<uint32_t, false, false>(a, n_units, 0, stream);
+        launch_variant<uint32_t, false>(a, n_units, 0, stream);
     }
     return hipGetLastError();
 }
