@@ -23,11 +23,14 @@
 // The end states are not kept: after the scans the emitting pass walks the admissible pairs again
 // and writes them in ascending token id.  Nothing here depends on the order in which atomics are
 // served (the only ones are ORs into the wave's own bitmap), so the CSR is deterministic.
+#include <type_traits>
+
 #include "internal.h"
 
 namespace fsmidx {
 
 constexpr int kWalkBatch = 4;          // gathers a lane has in flight when working off the queue
+constexpr int kWalkSlots = 8;          // most states whose survivors share one queue
 
 struct WalkArgs {
     const TokenRecord *tok;
@@ -43,6 +46,11 @@ struct WalkArgs {
     int32_t n_chunks;
 };
 
+// Queue entries of one wave: two states' worth with 16-bit table entries, one and a half with
+// 32-bit ones (what fits beside the rest in 64 KB of LDS per workgroup).
+template <typename E> struct QueueCap { static constexpr int value = 2 * kGroupTokens; };
+template <> struct QueueCap<uint32_t> { static constexpr int value = kGroupTokens + kGroupTokens / 2; };
+
 // LDS of one workgroup, after the table copy (TAB_LDS only).
 template <typename E>
 struct alignas(16) WalkShared {
@@ -50,16 +58,22 @@ struct alignas(16) WalkShared {
     uint16_t length[kGroupTokens];                    // their lengths (clamped to 65535: see the kernel)
     struct PerWave {
         E row[256];                                   // row q of the table
-        E state[kGroupTokens];                        // queue: state reached ...
-        uint16_t token[kGroupTokens];                 //        ... by this token of the group
-        uint64_t bits[kChunksPerWave];                // admissible tokens of the group from q
+        E state[QueueCap<E>::value];                  // queue: state reached ...
+        uint16_t token[QueueCap<E>::value];           //        ... by this token of the group | slot of the start state << 10
+        uint64_t bits[kWalkSlots][kChunksPerWave];    // per slot: admissible tokens of the group from that state
     } wave[kWavesPerBlock];
 };
 
 // E: narrowed entry type.  TAB_LDS: the whole table is first copied to LDS.
+//
+// The bytes after the first are a chain of dependent memory round trips, one per byte position,
+// each for ever fewer pairs.  So the survivors of several consecutive states share one queue
+// (as many states as leave room for a whole group of survivors of the next one, at most
+// kWalkSlots): the chain is then paid once for all of them.
 template <typename E, bool TAB_LDS>
 __global__ __launch_bounds__(kWave *kWavesPerBlock) void walk_pairs(const WalkArgs a)
 {
+    constexpr int kCap = QueueCap<E>::value;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     if (a.status->use_sets)
         return;                                                // uniform over the grid
@@ -108,112 +122,130 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void walk_pairs(const WalkAr
         __syncthreads();
         const bool group_has_eos = a.eos >= t_base && a.eos < t_base + kGroupTokens;
 
-        for (int32_t q = q_lo; q < q_hi; ++q) {
-            if (q == a.dead) {                                     // the dead state's row is empty
-                if (lane == 0)
-                    a.cnt[(int64_t)q * a.n_groups + g] = 0;
-                if (lane < kChunksPerWave)
-                    a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + lane] = 0;
-                continue;
-            }
-            // ---- byte 0 from row q in LDS
-            for (uint32_t c = (uint32_t)lane; c < n_classes; c += kWave)
-                my.row[c] = tab[(uint32_t)q * n_classes + c];
-            __builtin_amdgcn_wave_barrier();
-            uint32_t n = 0;                                        // pairs in the queue
+        // One byte position of the queue's pairs [b0, b0 + U * 64): look up, finish or keep.
+        // Compaction is in place: a pair is written at or before the place it was read from, and
+        // the reads of a call are issued before its writes.
+        auto advance = [&](auto batch, const uint32_t d, const uint32_t b0, const uint32_t n, uint32_t &kept) {
+            constexpr int U = decltype(batch)::value;
+            uint32_t s[U], t[U], c[U], len[U];
+            E s2[U];
+            bool valid[U];
 #pragma unroll
-            for (int k = 0; k < kChunksPerWave; ++k) {
-                const uint32_t len = first[k] >> 8;
-                const E s1 = my.row[first[k] & 255u];
-                const bool alive = len != 0 && s1 != dead_e;
-                const uint64_t done = __ballot(alive && len == 1u);
-                const uint64_t more = __ballot(alive && len > 1u);
-                if (lane == 0)
-                    my.bits[k] = done;
-                if (alive && len > 1u) {
-                    const uint32_t at = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(more >> 32),
-                                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)more, 0u));
-                    my.state[at] = s1;
-                    my.token[at] = (uint16_t)(k * kWave + lane);
-                }
-                n += (uint32_t)__popcll(more);
+            for (int u = 0; u < U; ++u) {
+                const uint32_t at = b0 + (uint32_t)(u * kWave + lane);
+                valid[u] = at < n;
+                s[u] = valid[u] ? (uint32_t)my.state[at] : 0u;
+                t[u] = valid[u] ? (uint32_t)my.token[at] : 0u;
             }
-            // EOS has no bytes: admissible exactly from accepting states
-            if (group_has_eos && a.accept[q] != 0 && lane == 0) {
-                const int32_t e = a.eos - t_base;
-                my.bits[e >> 6] |= 1ull << (e & 63);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t tt = t[u] & (uint32_t)(kGroupTokens - 1);
+                len[u] = sh.length[tt];
+                if (d < (uint32_t)kPackedClasses) {
+                    c[u] = (uint32_t)(sh.packed[tt] >> (8 * d)) & 255u;
+                } else {
+                    // (few walks get this far) the class string; the real length, which may exceed 16 bits
+                    c[u] = 0;
+                    if (valid[u]) {
+                        const TokenRecord rec = a.tok[t_base + (int32_t)tt];
+                        c[u] = a.cls[rec.offset + d];
+                        len[u] = rec.length;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                s2[u] = valid[u] ? tab[s[u] * n_classes + c[u]] : dead_e;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool alive = valid[u] && s2[u] != dead_e;
+                const bool done = alive && len[u] == d + 1u;
+                const bool more = alive && !done;
+                if (done) {
+                    const uint32_t tt = t[u] & (uint32_t)(kGroupTokens - 1);
+                    atomicOr(reinterpret_cast<unsigned long long *>(&my.bits[t[u] >> 10][tt >> 6]), 1ull << (tt & 63u));
+                }
+                const uint64_t m = __ballot(more);
+                if (more) {
+                    const uint32_t at = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                    my.state[at] = s2[u];
+                    my.token[at] = (uint16_t)t[u];
+                }
+                kept += (uint32_t)__popcll(m);
             }
             __builtin_amdgcn_wave_barrier();
-            // ---- bytes 1, 2, ...: the queue, kWalkBatch * 64 pairs at a time, compacted in place
-            //      (a pair is written at or before the place it was read from, and the reads of a
-            //      batch are issued before its writes)
+        };
+
+        for (int32_t q0 = q_lo; q0 < q_hi;) {
+            // ---- byte 0 of the next states, from their table rows in LDS, while the queue has room
+            //      for all 1024 pairs of one more state
+            uint32_t n = 0;                                        // pairs in the queue
+            int slots = 0;
+            while (q0 + slots < q_hi && slots < kWalkSlots && n + (uint32_t)kGroupTokens <= (uint32_t)kCap) {
+                const int32_t q = q0 + slots;
+                const bool is_dead = q == a.dead;                  // the dead state's row is empty
+                for (uint32_t c = (uint32_t)lane; c < n_classes; c += kWave)
+                    my.row[c] = tab[(uint32_t)q * n_classes + c];
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int k = 0; k < kChunksPerWave; ++k) {
+                    const uint32_t len = first[k] >> 8;
+                    const E s1 = my.row[first[k] & 255u];
+                    const bool alive = len != 0 && s1 != dead_e && !is_dead;
+                    const uint64_t done = __ballot(alive && len == 1u);
+                    const uint64_t more = __ballot(alive && len > 1u);
+                    if (lane == 0)
+                        my.bits[slots][k] = done;
+                    if (alive && len > 1u) {
+                        const uint32_t at = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(more >> 32),
+                                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)more, 0u));
+                        my.state[at] = s1;
+                        my.token[at] = (uint16_t)((uint32_t)(k * kWave + lane) | (uint32_t)slots << 10);
+                    }
+                    n += (uint32_t)__popcll(more);
+                }
+                // EOS has no bytes: admissible exactly from accepting states
+                if (group_has_eos && !is_dead && a.accept[q] != 0 && lane == 0) {
+                    const int32_t e = a.eos - t_base;
+                    my.bits[slots][e >> 6] |= 1ull << (e & 63);
+                }
+                __builtin_amdgcn_wave_barrier();                   // the row is read before the next state's is written
+                ++slots;
+            }
+            // ---- bytes 1, 2, ...
             for (uint32_t d = 1; n != 0; ++d) {
                 uint32_t kept = 0;
-                for (uint32_t b0 = 0; b0 < n; b0 += kWalkBatch * kWave) {
-                    uint32_t s[kWalkBatch], t[kWalkBatch], c[kWalkBatch], len[kWalkBatch];
-                    E s2[kWalkBatch];
-                    bool valid[kWalkBatch];
-#pragma unroll
-                    for (int u = 0; u < kWalkBatch; ++u) {
-                        const uint32_t at = b0 + (uint32_t)(u * kWave + lane);
-                        valid[u] = at < n;
-                        s[u] = valid[u] ? (uint32_t)my.state[at] : 0u;
-                        t[u] = valid[u] ? (uint32_t)my.token[at] : 0u;
+                for (uint32_t b0 = 0; b0 < n;) {
+                    if (n - b0 > (uint32_t)kWave) {
+                        advance(std::integral_constant<int, kWalkBatch>{}, d, b0, n, kept);
+                        b0 += kWalkBatch * kWave;
+                    } else {
+                        advance(std::integral_constant<int, 1>{}, d, b0, n, kept);
+                        b0 += kWave;
                     }
-#pragma unroll
-                    for (int u = 0; u < kWalkBatch; ++u) {
-                        len[u] = sh.length[t[u]];
-                        if (d < (uint32_t)kPackedClasses) {
-                            c[u] = (uint32_t)(sh.packed[t[u]] >> (8 * d)) & 255u;
-                        } else {
-                            // (few walks get this far) the class string; a token of 65535 bytes or more has its
-                            // real length in its record
-                            c[u] = 0;
-                            if (valid[u]) {
-                                const TokenRecord rec = a.tok[t_base + (int32_t)t[u]];
-                                c[u] = a.cls[rec.offset + d];
-                                len[u] = rec.length;
-                            }
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < kWalkBatch; ++u)
-                        s2[u] = valid[u] ? tab[s[u] * n_classes + c[u]] : dead_e;
-                    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                    for (int u = 0; u < kWalkBatch; ++u) {
-                        const bool alive = valid[u] && s2[u] != dead_e;
-                        const bool done = alive && len[u] == d + 1u;
-                        const bool more = alive && !done;
-                        if (done)
-                            atomicOr(reinterpret_cast<unsigned long long *>(&my.bits[t[u] >> 6]), 1ull << (t[u] & 63u));
-                        const uint64_t m = __ballot(more);
-                        if (more) {
-                            const uint32_t at = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                            my.state[at] = s2[u];
-                            my.token[at] = (uint16_t)t[u];
-                        }
-                        kept += (uint32_t)__popcll(m);
-                    }
-                    __builtin_amdgcn_wave_barrier();
                 }
                 n = kept;
             }
             __builtin_amdgcn_wave_barrier();
-            // ---- the bitmap row of (q, group) and its popcount
-            uint32_t count = 0;
-            if (lane < kChunksPerWave) {
-                const uint64_t word = my.bits[lane];
-                a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + lane] = word;
-                count = (uint32_t)__popcll(word);
-            }
+            // ---- the bitmap rows of (state, group) and their popcounts
+            for (int j = 0; j < slots; ++j) {
+                const int32_t q = q0 + j;
+                uint32_t count = 0;
+                if (lane < kChunksPerWave) {
+                    const uint64_t word = my.bits[j][lane];
+                    a.allow[(int64_t)q * a.n_chunks + g * kChunksPerWave + lane] = word;
+                    count = (uint32_t)__popcll(word);
+                }
 #pragma unroll
-            for (int o = kChunksPerWave / 2; o >= 1; o >>= 1)
-                count += __shfl_xor(count, o, kWave);
-            if (lane == 0)
-                a.cnt[(int64_t)q * a.n_groups + g] = count;
+                for (int o = kChunksPerWave / 2; o >= 1; o >>= 1)
+                    count += __shfl_xor(count, o, kWave);
+                if (lane == 0)
+                    a.cnt[(int64_t)q * a.n_groups + g] = count;
+            }
             __builtin_amdgcn_wave_barrier();
+            q0 += slots;
         }
     }
 }
@@ -252,7 +284,7 @@ hipError_t launch_walk(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab 
     const size_t tab_bytes = ((size_t)p.n_states * p.n_classes * p.entry_bytes + 15) / 16 * 16;
     a.tab_bytes = (uint32_t)(tab_bytes <= 0xFFFFFFFFu ? tab_bytes : 0);
     const int64_t n_units = (int64_t)p.n_groups * ((p.n_ranges + kWavesPerBlock - 1) / kWavesPerBlock);
-    const bool lds = tab_bytes <= 32 * 1024;
+    const bool lds = tab_bytes <= 12 * 1024;                       // beside the queues, within 64 KB per workgroup
     const size_t lds_bytes = lds ? tab_bytes : 0;
     if (p.entry_bytes == 2) {
         if (lds) launch_variant<uint16_t, true>(a, n_units, lds_bytes, stream);
