@@ -277,6 +277,63 @@ int fsmidx_masked_sample(const fsmidx_csr *index, const int32_t *states_dev, int
                          int32_t *tokens_out_dev, int32_t *states_out_dev, void *stream);
 
 /*
+ * Many automata in one index (Section 5: the index of a large grammar is built from many
+ * automata; also the serving case of many regular expressions against one vocabulary).
+ * fsmidx_union_dfa forms, on the device, the disjoint union of `n_dfas` automata (1..64) as ONE
+ * automaton that the build calls above take like any other:
+ *   - state s of automaton k becomes state  state_base[k] + s,  state_base[k] = the number of states
+ *     of the automata before it (state_base[n_dfas] = all states);
+ *   - two bytes are in one class of the union iff every automaton has them in one class; classes
+ *     are numbered in order of their smallest byte;
+ *   - every automaton's dead state becomes one: the union's dead state is the renumbered dead state
+ *     of the first automaton that has one (-1 if none has), and every transition into any
+ *     automaton's dead state leads there.
+ * The index of the union is the automata's own indices laid end to end (rows state_base[k] ..
+ * state_base[k+1] - 1 are automaton k's rows, end states renumbered the same way), built with the
+ * vocabulary's share of the work done once; a decode batch that mixes sequences of different
+ * automata is then masked with one fsmidx_mask_logits call on union state ids.
+ *   `dfas` is a HOST array of structs whose pointer members are DEVICE pointers.  The three output
+ * arrays are DEVICE memory of the caller: trans_out [trans_capacity] int32 (needs all states x the
+ * union's classes, at most 256 per state), byte_to_class_out [256], accept_out [all states].
+ * `workspace`: device, 256-byte aligned, fsmidx_union_workspace_bytes(n_dfas) bytes.  On success
+ * *union_out describes the union (its pointers are the output arrays) and state_base_host
+ * [n_dfas + 1] is filled.  The call synchronises the stream twice (the class count, then the
+ * device-side range checks of the inputs: FSMIDX_BAD_DEVICE_INPUT as for fsmidx_build_count);
+ * FSMIDX_OUTPUT_TOO_SMALL if trans_capacity does not hold the table (the message says how much).
+ */
+int fsmidx_union_workspace_bytes(int32_t n_dfas, size_t *bytes);
+int fsmidx_union_dfa(const fsmidx_dfa *dfas, int32_t n_dfas, int32_t *trans_out_dev, int64_t trans_capacity,
+                     uint8_t *byte_to_class_out_dev, uint8_t *accept_out_dev, void *workspace, size_t workspace_bytes,
+                     fsmidx_dfa *union_out, int32_t *state_base_host /* [n_dfas + 1] */, void *stream);
+
+/*
+ * Identical rows kept once (Section 5: redundant states make the index larger than it has to be).
+ * States whose rows of sigma are identical -- the same tokens with the same end states -- are
+ * interchangeable for masking and for tracking the state.  fsmidx_dedupe_rows finds them:
+ *     row_of_state[q]   = the number of q's row among the distinct rows, which are numbered in
+ *                         order of the smallest state that has them
+ *     unique_row_ptr[u] = first entry of distinct row u in the compact arrays that
+ *                         fsmidx_dedupe_fill writes ([n_unique + 1] entries are set; the array
+ *                         must hold n_states + 1)
+ * and returns the number of distinct rows and of their entries (one stream synchronisation; rows
+ * are grouped by a 64-bit hash and then compared entry by entry, so the result is exact).
+ * fsmidx_dedupe_fill then copies the distinct rows side by side into token_ids_out /
+ * next_states_out [nnz_unique] (asynchronous).  End states stay state ids: the row of an end state
+ * s is distinct row row_of_state[s].  {n_states = n_unique, row_ptr = unique_row_ptr, the compact
+ * arrays} is an fsmidx_csr that mask_logits, advance_states and the masked choices accept with
+ * row_of_state[state] in the place of the state.
+ *   `workspace`: device, 256-byte aligned, fsmidx_dedupe_workspace_bytes(n_states) bytes; it
+ * carries state from dedupe_rows to dedupe_fill.  index->allow_bits is not used.  n_states <= 2^26.
+ */
+int fsmidx_dedupe_workspace_bytes(int32_t n_states, size_t *bytes);
+int fsmidx_dedupe_rows(const fsmidx_csr *index, void *workspace, size_t workspace_bytes,
+                       int32_t *row_of_state_dev /* [n_states] */, int64_t *unique_row_ptr_dev /* [n_states + 1] */,
+                       int32_t *n_unique_host, int64_t *nnz_unique_host, void *stream);
+int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t workspace_bytes,
+                       const int64_t *unique_row_ptr_dev, int32_t *token_ids_out_dev, int32_t *next_states_out_dev,
+                       void *stream);
+
+/*
  * Kernel timing for benchmarks.  After fsmidx_profile_enable(1) the calling thread's build,
  * mask_logits, advance_states, masked_argmax and masked_sample calls bracket each phase's kernels
  * with HIP events on the stream they are given (enable(0) stops that; either call resets the

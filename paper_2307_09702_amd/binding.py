@@ -25,6 +25,8 @@ EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "f
            "fsmidx_build_count", "fsmidx_build_fill", "fsmidx_build_into", "fsmidx_build_allow_bits", "fsmidx_mask_logits",
            "fsmidx_advance_states", "fsmidx_masked_argmax_workspace_bytes", "fsmidx_masked_argmax", "fsmidx_masked_argmax_static",
            "fsmidx_masked_sample_workspace_bytes", "fsmidx_masked_sample",
+           "fsmidx_union_workspace_bytes", "fsmidx_union_dfa",
+           "fsmidx_dedupe_workspace_bytes", "fsmidx_dedupe_rows", "fsmidx_dedupe_fill",
            "fsmidx_profile_enable", "fsmidx_profile_read")
 
 
@@ -98,6 +100,13 @@ def load():
     lib.fsmidx_masked_sample_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
     lib.fsmidx_masked_sample.argtypes = [POINTER(CCsr), c_void_p, c_int32, c_void_p, c_int64, c_int32, c_void_p,
                                          c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
+    lib.fsmidx_union_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
+    lib.fsmidx_union_dfa.argtypes = [POINTER(CDfa), c_int32, c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_size_t,
+                                     POINTER(CDfa), POINTER(c_int32), c_void_p]
+    lib.fsmidx_dedupe_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
+    lib.fsmidx_dedupe_rows.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_int32),
+                                       POINTER(c_int64), c_void_p]
+    lib.fsmidx_dedupe_fill.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.fsmidx_profile_enable.argtypes = [ctypes.c_int]
     lib.fsmidx_profile_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64)]
     for name in EXPORTS:
@@ -207,12 +216,83 @@ def build_workspace_bytes(n_states: int, n_classes: int, n_tokens: int, n_bytes:
     return int(size.value)
 
 
+def _aligned(n_bytes: int, device):
+    """(tensor that owns the memory, 256-byte aligned address inside it)"""
+    import torch
+    buf = torch.empty(n_bytes + 256, dtype=torch.uint8, device=device)
+    return buf, (buf.data_ptr() + 255) & ~255
+
+
+class DeviceUnion:
+    """fsmidx_union_dfa: automata given as numpy (trans, byte_to_class, accept, dead) tuples are put
+    on the device and joined there into one automaton (device tensors ``trans``, ``byte_to_class``,
+    ``accept``; ``n_states``, ``n_classes``, ``dead_state``; ``state_base`` as a numpy array)."""
+
+    def __init__(self, automata, device="cuda:0", trans_capacity=None, stream=None):
+        import torch
+        self.device = torch.device(device)
+        to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.device)
+        self.parts = []
+        structs = (CDfa * len(automata))()
+        total = 0
+        for k, (trans, b2c, accept, dead) in enumerate(automata):
+            t = to(np.asarray(trans, dtype=np.int32)); b = to(np.asarray(b2c, dtype=np.uint8))
+            a = to(np.asarray(accept, dtype=np.uint8))
+            self.parts.append((t, b, a))
+            structs[k] = CDfa(t.data_ptr(), int(trans.shape[0]), int(trans.shape[1]), b.data_ptr(), a.data_ptr(), int(dead))
+            total += int(trans.shape[0])
+        if trans_capacity is None:
+            trans_capacity = total * 256
+        self.trans_full = torch.empty(max(trans_capacity, 1), dtype=torch.int32, device=self.device)
+        self.byte_to_class = torch.empty(256, dtype=torch.uint8, device=self.device)
+        self.accept = torch.empty(max(total, 1), dtype=torch.uint8, device=self.device)
+        need = c_size_t()
+        _check(load().fsmidx_union_workspace_bytes(len(automata), byref(need)))
+        self._ws, ws_ptr = _aligned(int(need.value), self.device)
+        out = CDfa()
+        base = (c_int32 * (len(automata) + 1))()
+        _check(load().fsmidx_union_dfa(structs, len(automata), self.trans_full.data_ptr(), int(trans_capacity),
+                                       self.byte_to_class.data_ptr(), self.accept.data_ptr(), ws_ptr, int(need.value),
+                                       byref(out), base, _stream_handle(stream)))
+        self.n_states, self.n_classes, self.dead_state = int(out.n_states), int(out.n_classes), int(out.dead_state)
+        self.trans = self.trans_full[:self.n_states * self.n_classes].view(self.n_states, self.n_classes)
+        self.state_base = np.array(list(base), dtype=np.int64)
+
+
+def dedupe_rows(csr: CCsr, device="cuda:0", stream=None):
+    """fsmidx_dedupe_rows + fsmidx_dedupe_fill on torch tensors.  Returns (row_of_state int32
+    [n_states], unique_row_ptr int64 [n_unique + 1], token_ids_u, next_states_u)."""
+    import torch
+    dev = torch.device(device)
+    n_states = int(csr.n_states)
+    need = c_size_t()
+    _check(load().fsmidx_dedupe_workspace_bytes(n_states, byref(need)))
+    ws, ws_ptr = _aligned(int(need.value), dev)
+    row_of = torch.empty(n_states, dtype=torch.int32, device=dev)
+    urp = torch.empty(n_states + 1, dtype=torch.int64, device=dev)
+    n_unique, nnz_unique = c_int32(), c_int64()
+    _check(load().fsmidx_dedupe_rows(byref(csr), ws_ptr, int(need.value), row_of.data_ptr(), urp.data_ptr(),
+                                     byref(n_unique), byref(nnz_unique), _stream_handle(stream)))
+    tok = torch.empty(max(int(nnz_unique.value), 1), dtype=torch.int32, device=dev)
+    nxt = torch.empty(max(int(nnz_unique.value), 1), dtype=torch.int32, device=dev)
+    _check(load().fsmidx_dedupe_fill(byref(csr), ws_ptr, int(need.value), urp.data_ptr(), tok.data_ptr(), nxt.data_ptr(),
+                                     _stream_handle(stream)))
+    torch.cuda.synchronize()
+    del ws
+    return row_of, urp[:int(n_unique.value) + 1], tok[:int(nnz_unique.value)], nxt[:int(nnz_unique.value)]
+
+
 class DeviceProblem:
-    """An automaton and a vocabulary resident in device memory (torch tensors own the bytes)."""
+    """An automaton and a vocabulary resident in device memory (torch tensors own the bytes).
+    ``trans``, ``byte_to_class`` and ``accept`` may also be torch tensors already on the device
+    (say, the arrays of a DeviceUnion)."""
 
     def __init__(self, trans, byte_to_class, accept, dead_state, vocab_bytes, offsets, eos_token_id=-1,
                  device="cuda:0"):
         import torch
+        if not isinstance(trans, np.ndarray) and hasattr(trans, "data_ptr"):
+            self._init_from_device(trans, byte_to_class, accept, dead_state, vocab_bytes, offsets, eos_token_id, device)
+            return
         arrs = _host_arrays(trans, byte_to_class, accept, vocab_bytes, offsets)
         self.n_states, self.n_classes = arrs[0].shape
         self.n_tokens = arrs[4].shape[0] - 1
@@ -221,6 +301,24 @@ class DeviceProblem:
         self.device = torch.device(device)
         to = lambda a: torch.from_numpy(a if a.size else np.zeros(1, a.dtype)).to(self.device)
         self.trans, self.byte_to_class, self.accept, self.vocab_bytes, self.offsets = map(to, arrs)
+        self.workspace_bytes = build_workspace_bytes(self.n_states, self.n_classes, self.n_tokens, self.n_bytes)
+        self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=self.device)
+        self._ws_ptr = (self.workspace.data_ptr() + 255) & ~255
+        self.row_ptr = torch.empty(self.n_states + 1, dtype=torch.int64, device=self.device)
+        self.dfa_struct, self.vocab_struct = _structs(self.trans, self.byte_to_class, self.accept, self.dead_state,
+                                                      self.vocab_bytes, self.offsets, self.eos_token_id, self.n_bytes)
+
+    def _init_from_device(self, trans, byte_to_class, accept, dead_state, vocab_bytes, offsets, eos_token_id, device):
+        import torch
+        self.device = torch.device(device)
+        self.n_states, self.n_classes = int(trans.shape[0]), int(trans.shape[1])
+        vb = np.ascontiguousarray(vocab_bytes, dtype=np.uint8)
+        off = np.ascontiguousarray(offsets, dtype=np.int64)
+        self.n_tokens, self.n_bytes = off.shape[0] - 1, int(vb.shape[0])
+        self.dead_state, self.eos_token_id = int(dead_state), int(eos_token_id)
+        self.trans, self.byte_to_class, self.accept = trans.contiguous(), byte_to_class, accept
+        to = lambda a: torch.from_numpy(a if a.size else np.zeros(1, a.dtype)).to(self.device)
+        self.vocab_bytes, self.offsets = to(vb), to(off)
         self.workspace_bytes = build_workspace_bytes(self.n_states, self.n_classes, self.n_tokens, self.n_bytes)
         self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=self.device)
         self._ws_ptr = (self.workspace.data_ptr() + 255) & ~255

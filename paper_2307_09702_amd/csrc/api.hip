@@ -745,6 +745,143 @@ int fsmidx_masked_argmax(const fsmidx_csr *index, const int32_t *states_dev, int
     return FSMIDX_OK;
 }
 
+int fsmidx_union_workspace_bytes(int32_t n_dfas, size_t *bytes)
+{
+    if (!bytes)
+        return fail(FSMIDX_INVALID_ARG, "bytes must not be NULL");
+    if (n_dfas < 1 || n_dfas > kMaxUnion)
+        return fail(FSMIDX_INVALID_ARG, "n_dfas must be in 1..%d (got %d)", kMaxUnion, n_dfas);
+    *bytes = 256 + (size_t)kMaxUnion * 256;
+    return FSMIDX_OK;
+}
+
+int fsmidx_union_dfa(const fsmidx_dfa *dfas, int32_t n_dfas, int32_t *trans_out_dev, int64_t trans_capacity,
+                     uint8_t *byte_to_class_out_dev, uint8_t *accept_out_dev, void *workspace, size_t workspace_bytes,
+                     fsmidx_dfa *union_out, int32_t *state_base_host, void *stream_v)
+{
+    size_t need = 0;
+    if (int rc = fsmidx_union_workspace_bytes(n_dfas, &need))
+        return rc;
+    if (!dfas || !trans_out_dev || !byte_to_class_out_dev || !accept_out_dev || !union_out || !state_base_host)
+        return fail(FSMIDX_INVALID_ARG, "dfas, the three output arrays, union_out and state_base_host must not be NULL");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return fail(FSMIDX_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    int64_t total = 0;
+    int32_t union_dead = -1;
+    for (int32_t k = 0; k < n_dfas; ++k) {
+        const fsmidx_dfa &d = dfas[k];
+        if (int rc = check_sizes(d.n_states, d.n_classes, 0, 0))
+            return rc;
+        if (!d.trans || !d.byte_to_class || !d.accept)
+            return fail(FSMIDX_INVALID_ARG, "automaton %d: trans, byte_to_class and accept must not be NULL", k);
+        if (d.dead_state < -1 || d.dead_state >= d.n_states)
+            return fail(FSMIDX_INVALID_ARG, "automaton %d: dead_state must be -1 or in [0, n_states)", k);
+        state_base_host[k] = (int32_t)total;
+        if (union_dead < 0 && d.dead_state >= 0)
+            union_dead = (int32_t)total + d.dead_state;
+        total += d.n_states;
+        if (total > 0x7FFFFFFFll)
+            return fail(FSMIDX_INVALID_ARG, "the union has more than 2^31 - 1 states");
+    }
+    state_base_host[n_dfas] = (int32_t)total;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    FSMIDX_HIP(launch_union_classes(dfas, n_dfas, byte_to_class_out_dev, ws, stream));
+    uint32_t words[2] = {0, 0};
+    FSMIDX_HIP(hipMemcpyAsync(words, ws, sizeof(words), hipMemcpyDeviceToHost, stream));
+    FSMIDX_HIP(hipStreamSynchronize(stream));
+    if (words[1])
+        return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(words[1]), words[1]);
+    const int32_t n_classes = (int32_t)words[0];
+    if (n_classes < 1 || n_classes > 256)
+        return fail(FSMIDX_HIP_ERROR, "the union's class count came back as %d", n_classes);
+    if (total * n_classes > trans_capacity)
+        return fail(FSMIDX_OUTPUT_TOO_SMALL, "the union's table has %lld x %d entries, trans_out holds %lld",
+                    (long long)total, n_classes, (long long)trans_capacity);
+    if (total * n_classes > 0x7FFFFFFFll)
+        return fail(FSMIDX_INVALID_ARG, "transition table too large: n_states*n_classes must be < 2^31");
+    FSMIDX_HIP(launch_union_table(dfas, n_dfas, state_base_host, union_dead, n_classes, trans_out_dev, accept_out_dev, ws,
+                                  stream));
+    FSMIDX_HIP(hipMemcpyAsync(words, ws, sizeof(words), hipMemcpyDeviceToHost, stream));
+    FSMIDX_HIP(hipStreamSynchronize(stream));
+    if (words[1])
+        return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(words[1]), words[1]);
+    union_out->trans = trans_out_dev;
+    union_out->n_states = (int32_t)total;
+    union_out->n_classes = n_classes;
+    union_out->byte_to_class = byte_to_class_out_dev;
+    union_out->accept = accept_out_dev;
+    union_out->dead_state = union_dead;
+    return FSMIDX_OK;
+}
+
+int fsmidx_dedupe_workspace_bytes(int32_t n_states, size_t *bytes)
+{
+    if (!bytes)
+        return fail(FSMIDX_INVALID_ARG, "bytes must not be NULL");
+    if (n_states < 1 || n_states > kDedupeMaxStates)
+        return fail(FSMIDX_INVALID_ARG, "n_states must be in 1..%d (got %d)", kDedupeMaxStates, n_states);
+    *bytes = align256(dedupe_workspace_bytes(n_states));
+    return FSMIDX_OK;
+}
+
+int fsmidx_dedupe_rows(const fsmidx_csr *index, void *workspace, size_t workspace_bytes, int32_t *row_of_state_dev,
+                       int64_t *unique_row_ptr_dev, int32_t *n_unique_host, int64_t *nnz_unique_host, void *stream_v)
+{
+    if (int rc = check_rows(index))
+        return rc;
+    size_t need = 0;
+    if (int rc = fsmidx_dedupe_workspace_bytes(index->n_states, &need))
+        return rc;
+    if (!row_of_state_dev || !unique_row_ptr_dev || !n_unique_host || !nnz_unique_host)
+        return fail(FSMIDX_INVALID_ARG, "row_of_state, unique_row_ptr, n_unique_host and nnz_unique_host must not be NULL");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return fail(FSMIDX_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    // Rows are grouped by a 64-bit hash and then compared entry by entry; two different rows with
+    // one hash (a chance of about states^2 / 2^64) make the pass start again with another seed.
+    for (uint64_t attempt = 0; attempt < 4; ++attempt) {
+        FSMIDX_HIP(launch_dedupe(*index, ws, 0x243F6A8885A308D3ull + attempt * 0x9E3779B97F4A7C15ull, row_of_state_dev,
+                                 unique_row_ptr_dev, stream));
+        int64_t result[3] = {0, 0, 0};
+        FSMIDX_HIP(hipMemcpyAsync(result, ws, sizeof(result), hipMemcpyDeviceToHost, stream));
+        FSMIDX_HIP(hipStreamSynchronize(stream));
+        if (result[2] == 0) {
+            *n_unique_host = (int32_t)result[0];
+            *nnz_unique_host = result[1];
+            return FSMIDX_OK;
+        }
+    }
+    return fail(FSMIDX_HIP_ERROR, "row hashes collided four times in a row");
+}
+
+int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t workspace_bytes,
+                       const int64_t *unique_row_ptr_dev, int32_t *token_ids_out_dev, int32_t *next_states_out_dev,
+                       void *stream_v)
+{
+    if (int rc = check_rows(index))
+        return rc;
+    size_t need = 0;
+    if (int rc = fsmidx_dedupe_workspace_bytes(index->n_states, &need))
+        return rc;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need)
+        return fail(FSMIDX_INVALID_ARG, "workspace must be the one fsmidx_dedupe_rows has filled");
+    if (!unique_row_ptr_dev)
+        return fail(FSMIDX_INVALID_ARG, "unique_row_ptr must not be NULL");
+    if (index->nnz == 0)
+        return FSMIDX_OK;
+    if (!token_ids_out_dev || !next_states_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "token_ids_out and next_states_out must not be NULL when the index has entries");
+    FSMIDX_HIP(launch_dedupe_copy(*index, const_cast<char *>(static_cast<const char *>(workspace)), unique_row_ptr_dev,
+                                  token_ids_out_dev, next_states_out_dev, static_cast<hipStream_t>(stream_v)));
+    return FSMIDX_OK;
+}
+
 int fsmidx_masked_sample_workspace_bytes(int32_t batch, size_t *bytes)
 {
     if (!bytes)

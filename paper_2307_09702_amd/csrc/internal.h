@@ -41,6 +41,9 @@ constexpr int kLongRow = 512;         // entries of one (state, block) above whi
 constexpr int kArgmaxSplits = 64;
 constexpr int kArgmaxMaxBatch = 1 << 24;   // batch * kArgmaxSplits workgroups must fit a grid
 
+constexpr int kMaxUnion = 64;              // automata that one union call takes (their pointers travel as kernel arguments)
+constexpr int kDedupeMaxStates = 1 << 26;  // states * 16 workgroups must fit a grid
+
 // Bits of the device-side input check word.
 enum : uint32_t {
     kBadTransition = 1u,   // table entry outside [0, n_states)
@@ -155,6 +158,19 @@ hipError_t launch_argmax(const fsmidx_csr &csr, const int32_t *states, int32_t b
 hipError_t launch_sample(const fsmidx_csr &csr, const int32_t *states, int32_t batch, const void *logits,
                          int64_t row_stride, int32_t dtype, const float *uniforms, uint64_t *partial, double *sums,
                          int32_t *tokens_out, int32_t *states_out, hipStream_t stream);
+
+// union of automata; ws: 256 bytes of words ([0] classes of the union, [1] check flags) + kMaxUnion * 256 class ids
+hipError_t launch_union_classes(const fsmidx_dfa *dfas, int32_t n_dfas, uint8_t *union_b2c, char *ws,
+                                hipStream_t stream);
+hipError_t launch_union_table(const fsmidx_dfa *dfas, int32_t n_dfas, const int32_t *state_base, int32_t union_dead,
+                              int32_t n_union_classes, int32_t *trans_out, uint8_t *accept_out, char *ws,
+                              hipStream_t stream);
+// identical rows; ws starts with int64 [3]: distinct rows, their entries, collision flag
+size_t dedupe_workspace_bytes(int32_t n_states);
+hipError_t launch_dedupe(const fsmidx_csr &csr, char *ws, uint64_t seed, int32_t *row_of_state,
+                         int64_t *unique_row_ptr, hipStream_t stream);
+hipError_t launch_dedupe_copy(const fsmidx_csr &csr, char *ws, const int64_t *unique_row_ptr, int32_t *token_ids_out,
+                              int32_t *next_states_out, hipStream_t stream);
 
 int fail(int code, const char *fmt, ...);   // records the thread's last error, returns code
 
