@@ -41,7 +41,7 @@ typedef enum {
 /*
  * The automaton (Q, Sigma, delta, q0, F) of Section 3, Definition 1, as a dense table over byte
  * classes: delta(s, b) = trans[s * n_classes + byte_to_class[b]].  q0 is not needed: every state
- * is indexed as a possible starting point (Section 3, "starting in every viable FSM state").
+ * is indexed as a possible starting point (Section 3: a walk may begin in any state).
  * The paper's "delta(r, v_i) = empty" (Algorithm 3) is encoded by one absorbing state
  * `dead_state`; -1 means the automaton is total and nothing is ever rejected.
  */
@@ -63,7 +63,7 @@ typedef struct {
 typedef struct {
     const uint8_t *bytes;          /* [n_bytes]                                                        */
     const int64_t *offsets;        /* [n_tokens + 1], offsets[0] = 0, non-decreasing, last = n_bytes   */
-    int32_t        n_tokens;       /* 0 .. 2^31-1                                                      */
+    int32_t        n_tokens;       /* 0 .. 2^30                                                        */
     int32_t        eos_token_id;   /* -1 or in [0, n_tokens)                                           */
     int64_t        n_bytes;        /* 0 .. 2^31-1                                                      */
 } fsmidx_vocab;
@@ -129,7 +129,10 @@ void fsmidx_free_index(fsmidx_index *index);
  *                                    automaton that branches deeply makes the walk count again
  *                                    another way, at most twice, with one more each time)
  *   caller allocates token_ids[nnz], next_states[nnz]
- *   fsmidx_build_fill             -> walks again and writes the entries (asynchronous)
+ *   fsmidx_build_fill             -> walks again and writes the entries (asynchronous; `nnz` must be the
+ *                                    count fsmidx_build_count returned: the call cannot wait for the
+ *                                    device, so with a smaller nnz it returns FSMIDX_OK and the kernel,
+ *                                    which checks the count against nnz itself, writes nothing)
  *
  * In fsmidx_build_count / fsmidx_build_fill the POINTER members of `dfa` and `vocab` are device
  * pointers; the scalar members are read on the host.  The host cannot inspect device data, so
@@ -187,8 +190,11 @@ int fsmidx_build_allow_bits(int32_t n_states, int32_t n_classes, int32_t n_token
  *   a state with an empty row (e.g. the dead state) -> everything becomes -inf
  * With index->allow_bits the kernel reads one bitmap word per 64 tokens; without it, it locates
  * the row's token ids by search.  Both give the same result.
- * `logits_out` may be the same pointer as `logits_in` (in place: only -inf is written) but must
- * not overlap it in any other way.  All pointers are DEVICE pointers; buffers must be aligned to
+ * `logits_out` may be the same pointer as `logits_in` but must not overlap it in any other way.
+ * In place the result is the same bits; which bytes are stored differs by type: binary32 stores
+ * -inf over removed tokens only and reads no logits; bfloat16 also reads and rewrites, unchanged,
+ * the kept tokens that share a 16-byte vector with removed ones (eight 2-byte stores cost more than
+ * the read), so in place no other stream may write kept bfloat16 logits meanwhile.  All pointers are DEVICE pointers; buffers must be aligned to
  * the element size.  Asynchronous on `stream`.
  */
 int fsmidx_mask_logits(const fsmidx_csr *index, const int32_t *states_dev, int32_t batch,

@@ -146,7 +146,8 @@ static void run_rows(const problem_t *p, int n_threads, int64_t *row_count, cons
  * Pass 1: row_ptr[0..n_states] (exclusive prefix sums of the row sizes, row_ptr[n_states] = nnz).
  * counters[0] = W_bf   transition evaluations of the early-exit walk over all pairs,
  * counters[1] = W_inv  the same minus the walks that fail on their first byte (the walks
- *                      that Algorithm 3's "states that read v0" filter never starts).
+ *                      that Algorithm 3's restriction to start states able to read v0 never
+ *                      starts).
  * States are statically split over n_threads threads; every thread runs the same loops.
  */
 int64_t oracle_index_count(const int32_t *trans, int32_t n_states, int32_t n_classes,

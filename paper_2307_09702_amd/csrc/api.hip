@@ -685,9 +685,9 @@ int fsmidx_mask_logits(const fsmidx_csr *index, const int32_t *states_dev, int32
     const size_t elem = dtype == 0 ? 4 : 2;
     if ((reinterpret_cast<uintptr_t>(logits_in) | reinterpret_cast<uintptr_t>(logits_out)) & (elem - 1))
         return fail(FSMIDX_INVALID_ARG, "logits buffers must be aligned to the element size");
-    const int64_t segs = ((int64_t)index->n_tokens + 2047) / 2048;     // smallest segment of any kernel
+    const int64_t segs = ((int64_t)index->n_tokens + 511) / 512;       // smallest segment of any mask kernel
     if (segs * batch > 0x7FFFFFFFll)
-        return fail(FSMIDX_INVALID_ARG, "batch * ceil(n_tokens / 2048) must be < 2^31");
+        return fail(FSMIDX_INVALID_ARG, "batch * ceil(n_tokens / 512) must be < 2^31");
     prof_mark(4 + dtype, 0, static_cast<hipStream_t>(stream_v));
     FSMIDX_HIP(launch_mask(*index, states_dev, batch, logits_in, logits_out, row_stride, dtype,
                            static_cast<hipStream_t>(stream_v)));

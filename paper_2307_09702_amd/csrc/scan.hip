@@ -1,5 +1,5 @@
-// Prefix sums that turn the per-(state, token group) counts into CSR positions (Algorithm 4's
-// "sigma(z_0) <- sigma(z_0) U v", made order-preserving).
+// Prefix sums that turn the per-(state, token group) counts into CSR positions (the bookkeeping
+// behind Algorithm 4's union of v into sigma(z_0), made order-preserving).
 //
 //  scan_groups : one wave per state; exclusive scan of that state's counts over the token groups,
 //                written back in place, and the row total.
