@@ -15,10 +15,11 @@
 //      the maximum over the slices and looks up token and end state.  No atomics, deterministic.
 //
 //  masked_sample    the sampling step of Algorithm 2: one draw per sequence from the softmax over the
-//      row's entries, by inversion with a uniform number the caller supplies.  Three passes over the
-//      row: the slice maxima (the same kernel as for masked_argmax), the slice sums of
-//      w = exp(logit - max), and a last kernel, one wave per sequence, that finds the slice in which
-//      the cumulative weight crosses u * total and walks that slice in order.  Weights are
+//      row's entries, by inversion with a uniform number the caller supplies.  One pass over the
+//      row gives every slice's maximum and the sum of its weights relative to that maximum (a
+//      running maximum, the sum rescaled when it rises); a second kernel, one wave per sequence,
+//      brings the slice sums to the row's maximum, finds the slice in which the cumulative weight
+//      crosses u * total and walks that slice in order with w = exp(logit - max).  Weights are
 //      binary32 exponentials, every sum is binary64.
 #include "internal.h"
 
@@ -224,47 +225,68 @@ __device__ __forceinline__ double logit_weight(uint32_t u, float top)
     return (double)expf(x - top);
 }
 
-// grid as for argmax_slices: the sum of the weights of every slice
+// grid as for argmax_slices: the largest logit of every slice and the sum of the slice's weights
+// relative to it, in ONE pass over the slice's entries: a lane keeps a running maximum and
+// rescales its sum whenever the maximum rises, and the lanes' pairs are merged the same way.
+// partial = the maximum's key << 32 (0: the slice has no entries), sums = sum of exp(logit - slice
+// maximum) (1 for a logit equal to it).
 template <typename T>
-__global__ __launch_bounds__(kWave) void sample_sums(const int64_t *__restrict__ row_ptr,
-                                                     const int32_t *__restrict__ token_ids, int32_t n_states,
-                                                     int32_t n_tokens, const int32_t *__restrict__ states,
-                                                     const T *__restrict__ logits, int64_t row_stride,
-                                                     const uint64_t *__restrict__ partial, double *__restrict__ sums)
+__global__ __launch_bounds__(kWave) void sample_slices(const int64_t *__restrict__ row_ptr,
+                                                       const int32_t *__restrict__ token_ids, int32_t n_states,
+                                                       int32_t n_tokens, const int32_t *__restrict__ states,
+                                                       const T *__restrict__ logits, int64_t row_stride,
+                                                       uint64_t *__restrict__ partial, double *__restrict__ sums)
 {
     const int lane = threadIdx.x;
     const int32_t b = blockIdx.x / kArgmaxSplits;
     const int32_t slice = blockIdx.x % kArgmaxSplits;
-    const uint64_t best = row_best(partial, b, lane);
-    double sum = 0.0;
-    const float top = key_value((uint32_t)(best >> 32));
-    if (best != 0 && top != -INFINITY) {
-        int64_t lo, n, i0, i1;
-        bool whole;
-        row_of(row_ptr, n_states, n_tokens, states[b], lo, n, whole);
-        slice_range(n, slice, i0, i1);
-        const T *row = logits + (int64_t)b * row_stride;
-        constexpr int kUnroll = 8;
-        for (int64_t i = i0 + lane; i < i1; i += kUnroll * kWave) {
-            uint32_t t[kUnroll], u[kUnroll];
+    int64_t lo, n, i0, i1;
+    bool whole;
+    row_of(row_ptr, n_states, n_tokens, states[b], lo, n, whole);
+    slice_range(n, slice, i0, i1);
+    const T *row = logits + (int64_t)b * row_stride;
+    float top = -INFINITY;                                 // of this lane's entries so far
+    double sum = 0.0;                                      // of their weights relative to `top`
+    constexpr int kUnroll = 8;
+    for (int64_t i = i0 + lane; i < i1; i += kUnroll * kWave) {
+        uint32_t t[kUnroll], u[kUnroll];
 #pragma unroll
-            for (int k = 0; k < kUnroll; ++k) {
-                const int64_t at = i + k * kWave;
-                t[k] = 0xFFFFFFFFu;
-                if (at < i1)
-                    t[k] = whole ? (uint32_t)at : (uint32_t)token_ids[lo + at];
+        for (int k = 0; k < kUnroll; ++k) {
+            const int64_t at = i + k * kWave;
+            t[k] = 0xFFFFFFFFu;
+            if (at < i1)
+                t[k] = whole ? (uint32_t)at : (uint32_t)token_ids[lo + at];
+        }
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k)
+            u[k] = t[k] < (uint32_t)n_tokens ? logit_bits<T>(row + t[k]) : 0xFF800000u;
+#pragma unroll
+        for (int k = 0; k < kUnroll; ++k) {
+            if ((u[k] & 0x7FFFFFFFu) > 0x7F800000u || u[k] == 0xFF800000u)
+                continue;                                  // NaN counts as -inf, and -inf weighs nothing
+            const float x = __uint_as_float(u[k]);
+            if (x > top) {
+                sum = (top == -INFINITY ? 0.0 : sum * (double)expf(top - x)) + 1.0;
+                top = x;
+            } else {
+                sum += x == top ? 1.0 : (double)expf(x - top);
             }
-#pragma unroll
-            for (int k = 0; k < kUnroll; ++k)
-                u[k] = t[k] < (uint32_t)n_tokens ? logit_bits<T>(row + t[k]) : 0xFF800000u;
-#pragma unroll
-            for (int k = 0; k < kUnroll; ++k)
-                sum += logit_weight(u[k], top);            // entries past the slice read -inf: weight 0
         }
     }
+    // merge the lanes: the slice's maximum, every lane's sum rescaled to it
+    float all = top;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1)
+        all = fmaxf(all, __shfl_xor(all, d, kWave));
+    if (top != all)
+        sum = top == -INFINITY ? 0.0 : sum * (double)expf(top - all);
     sum = wave_sum_f64(sum);
-    if (lane == 0)
+    if (lane == 0) {
+        const bool any = i1 > i0;
+        // (a slice of nothing but -inf and NaN reports -inf as its maximum, with weight 0)
+        partial[(int64_t)b * kArgmaxSplits + slice] = any ? (uint64_t)logit_key(__float_as_uint(all)) << 32 | 1u : 0ull;
         sums[(int64_t)b * kArgmaxSplits + slice] = sum;
+    }
 }
 
 // one wave per sequence: the slice in which the cumulative weight crosses the threshold, then the
@@ -296,8 +318,12 @@ __global__ __launch_bounds__(kWave) void sample_pick(const int64_t *__restrict__
     bool whole;
     row_of(row_ptr, n_states, n_tokens, s, lo, n, whole);
     const float top = key_value((uint32_t)(best >> 32));
-    // inclusive prefix sums of the slice sums
-    const double mine = sums[(int64_t)b * kArgmaxSplits + lane];
+    // inclusive prefix sums of the slice sums, each brought from its slice's maximum to the row's
+    const uint64_t own_word = partial[(int64_t)b * kArgmaxSplits + lane];
+    const float own_top = key_value((uint32_t)(own_word >> 32));
+    double mine = own_word != 0 ? sums[(int64_t)b * kArgmaxSplits + lane] : 0.0;
+    if (mine != 0.0 && own_top != top)
+        mine *= (double)expf(own_top - top);
     double incl = mine;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
@@ -428,19 +454,15 @@ hipError_t launch_sample(const fsmidx_csr &csr, const int32_t *states, int32_t b
     const dim3 grid((unsigned)batch * kArgmaxSplits);
     if (dtype == 0) {
         const uint32_t *x = static_cast<const uint32_t *>(logits);
-        hipLaunchKernelGGL(argmax_slices<uint32_t>, grid, dim3(kArgmaxThreads), 0, stream, csr.row_ptr, csr.token_ids,
-                           csr.n_states, csr.n_tokens, states, x, row_stride, partial);
-        hipLaunchKernelGGL(sample_sums<uint32_t>, grid, dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids, csr.n_states,
-                           csr.n_tokens, states, x, row_stride, partial, sums);
+        hipLaunchKernelGGL(sample_slices<uint32_t>, grid, dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids,
+                           csr.n_states, csr.n_tokens, states, x, row_stride, partial, sums);
         hipLaunchKernelGGL(sample_pick<uint32_t>, dim3(batch), dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids,
                            csr.next_states, csr.n_states, csr.n_tokens, states, x, row_stride, uniforms, partial, sums,
                            tokens_out, states_out);
     } else {
         const uint16_t *x = static_cast<const uint16_t *>(logits);
-        hipLaunchKernelGGL(argmax_slices<uint16_t>, grid, dim3(kArgmaxThreads), 0, stream, csr.row_ptr, csr.token_ids,
-                           csr.n_states, csr.n_tokens, states, x, row_stride, partial);
-        hipLaunchKernelGGL(sample_sums<uint16_t>, grid, dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids, csr.n_states,
-                           csr.n_tokens, states, x, row_stride, partial, sums);
+        hipLaunchKernelGGL(sample_slices<uint16_t>, grid, dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids,
+                           csr.n_states, csr.n_tokens, states, x, row_stride, partial, sums);
         hipLaunchKernelGGL(sample_pick<uint16_t>, dim3(batch), dim3(kWave), 0, stream, csr.row_ptr, csr.token_ids,
                            csr.next_states, csr.n_states, csr.n_tokens, states, x, row_stride, uniforms, partial, sums,
                            tokens_out, states_out);
