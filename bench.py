@@ -210,6 +210,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true",
                     help="skip the oracle legs (the roofline then uses the pair count as work)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="for profilers: leave out what is timed beside the step (other configs, index-size calls), so "
+                         "that every kernel name in a trace belongs to the step's workload")
     ap.add_argument("--workload", default="C3", choices=("C3", "C4b"),
                     help="C4b: only the build of the 20,000-state automaton, for profilers")
     args = ap.parse_args()
@@ -372,8 +375,8 @@ def main():
     # in-place masking writes -inf over every removed element and reads one bitmap bit per element
     mask_bytes = {e: (batch * n_vocab - kept) * e + batch * n_vocab // 8 for e in (4, 2)}
     oop_bytes = {e: batch * n_vocab * e + kept * e + batch * n_vocab // 8 for e in (4, 2)}
-    big = big_config_block(B, W, torch, dev, with_oracle=ref is not None)
-    reduced = reduce_block(B, W, torch, dev, csr, d.n_states, nnz)
+    big = None if args.step_only else big_config_block(B, W, torch, dev, with_oracle=ref is not None)
+    reduced = None if args.step_only else reduce_block(B, W, torch, dev, csr, d.n_states, nnz)
 
     # The two heavy kernels of the build and what bounds each:
     #  - the counting walk decides all pairs: transition lookups of the early-exit walk (W_bf, from
