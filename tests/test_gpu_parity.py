@@ -209,6 +209,46 @@ def test_table_sizes_around_the_lds_limit(gpu, oracle_mod):
         assert_same_index(ref, row_ptr, tok, nxt, f"Q={n_live}")
 
 
+@pytest.mark.parametrize("n_live,n_classes,p_live,dead,what", [
+    (300, 64, 0.3, "last", "a few live classes per state"),
+    (300, 64, 0.5, "last", "half of the classes live"),
+    (300, 64, 0.9, "last", "most pairs survive the first byte: a queue per state"),
+    (150, 64, 1.0, "none", "no dead state: every class is live"),
+    (300, 64, 0.4, "middle", "dead state in the middle"),
+    (400, 33, 0.4, "last", "odd number of classes"),
+    (7000, 2, 0.8, "last", "two classes, many states"),
+])
+def test_dense_walk_with_the_table_in_memory(gpu, oracle_mod, n_live, n_classes, p_live, dead, what):
+    """16-bit states, at most 64 classes and a table beyond 12 KB: the lane-per-pair walk whose
+    lookups after the first byte are gathers from memory, with few and with many survivors per state."""
+    rng = np.random.default_rng([n_live, n_classes, int(p_live * 100)])
+    dfa = W.random_dfa(rng, n_live, n_classes, p_live)
+    if dead == "none":
+        dfa = DFA(np.ascontiguousarray(dfa.trans[:n_live]), dfa.byte_to_class, dfa.accept[:n_live], dead=-1)
+    elif dead == "middle":
+        perm = rng.permutation(n_live + 1)
+        inv = np.argsort(perm)
+        dfa = DFA(perm[dfa.trans[inv]].astype(np.int32), dfa.byte_to_class, dfa.accept[inv], dead=int(perm[n_live]))
+    assert dfa.trans.size * 2 > 12 * 1024
+    vocab = W.bpe_like_vocab(rng, 2900, 4.0, 40)                  # three token groups, the last ragged; tokens past 8 bytes
+    eos = 1500
+    ref = oracle_index(oracle_mod, dfa, vocab, eos)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, eos)
+    assert_same_index(ref, row_ptr, tok, nxt, what)
+    assert ref.nnz > 0
+
+
+def test_dense_walk_many_states_per_wave(gpu, oracle_mod):
+    """Enough (state, token group) units that a wave walks more consecutive states than it keeps
+    bitmap rows for at a time."""
+    rng = np.random.default_rng(3000)
+    dfa = W.random_dfa(rng, 3000, 64, 0.3)
+    vocab = W.bpe_like_vocab(rng, 100_000, 4.5, 32)
+    ref = oracle_index(oracle_mod, dfa, vocab, 77_777)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, 77_777)
+    assert_same_index(ref, row_ptr, tok, nxt, "18 states per wave")
+
+
 # ----------------------------------------------------------------------------- choice of the walk
 
 def cyclic_dfa(n_live, steps, n_classes=None):
