@@ -190,7 +190,33 @@ def reduce_block(B, W, torch, dev, csr_large, n_states_large, nnz_large):
     t0 = time.perf_counter()
     row_of_l, urp_l, tok_l, nxt_l = B.dedupe_rows(csr_large)
     dedupe_large_ms = (time.perf_counter() - t0) * 1e3
+    # reachable-only index (Section 3, the remark after Algorithm 4): the large config from its start
+    # state, with its whole vocabulary and with one that has no one-letter and one-digit tokens
+    def reachable(csr, start, n=5):
+        reach, n_reached = B.reachable_states(csr, [start])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            reach, n_reached = B.reachable_states(csr, [start])
+        reach_ms = (time.perf_counter() - t0) / n * 1e3
+        t0 = time.perf_counter()
+        ptr, tok_r, nxt_r = B.restrict_rows(csr, reach)
+        restrict_ms = (time.perf_counter() - t0) * 1e3
+        return {"states": int(csr.n_states), "reachable": n_reached, "entries": int(csr.nnz), "entries_kept": int(tok_r.numel()),
+                "reachable_states_call_ms_host_clock": reach_ms, "restrict_calls_ms_host_clock": restrict_ms}
+    large = W.config_large()
+    reach_large = reachable(csr_large, large.dfa.start)
+    lens = np.diff(large.vocab.offsets)
+    first = large.vocab.bytes[np.minimum(large.vocab.offsets[:-1], large.vocab.bytes.size - 1)]
+    alnum = np.isin(first, np.frombuffer(b"abcdefghijklmnopqrstuvwxyzABCDEFGHIJKLMNOPQRSTUVWXYZ0123456789", np.uint8))
+    some = W.Vocab.from_tokens([large.vocab.token(t) for t in np.flatnonzero((lens >= 2) | ((lens == 1) & ~alnum))])
+    prob_s = B.DeviceProblem(large.dfa.trans, large.dfa.byte_to_class, large.dfa.accept, large.dfa.dead, some.bytes,
+                             some.offsets, -1)
+    csr_s, tok_s, nxt_s = prob_s.build()
+    reach_some = reachable(csr_s, large.dfa.start)
+    reach_some["vocabulary"] = "C3-large's tokens without the one-letter and one-digit ones (%d tokens)" % some.n_tokens
     return {
+        "reachable_only": {"C3-large": reach_large, "C3-large, no one-character alphanumeric tokens": reach_some},
         "union": {"automata": 8, "states": u.n_states, "classes": u.n_classes, "vocabulary": vocab.n_tokens,
                   "pairs": u.n_states * vocab.n_tokens, "nnz": union_nnz, "fsmidx_union_dfa_ms_host_clock": union_call_ms,
                   "one_build_ms": one_ms, "eight_builds_one_after_the_other_ms": sum(t for t, _ in separate),

@@ -340,6 +340,40 @@ int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t wo
                        void *stream);
 
 /*
+ * The reachable-only index (Section 3, the paragraph after Algorithm 4: the index needs a row per
+ * state in principle, but not every state is ever represented by a vocabulary string; Section 2.2,
+ * Algorithm 2: a generation starts in q_0 and moves to the end state stored with each sampled
+ * token).  The states a generation can be in are those reachable from q_0 through rows of the
+ * index; only their rows are ever read.
+ *   fsmidx_reachable_states marks them: reach_out[q] = 1 if some sequence of vocabulary tokens
+ * leads from one of the start states to q (the start states themselves included), else 0, and
+ * *n_reached_host = their number.  `start_states_host` is a HOST array of n_starts state ids in
+ * [0, n_states) (FSMIDX_INVALID_ARG otherwise); `index` is a complete index (device pointers,
+ * allow_bits not used); reach_out_dev [n_states] is DEVICE memory.  A breadth-first search on the
+ * device; the call synchronises the stream once per 8 to 64 levels and once at the end.  End states
+ * outside [0, n_states) (an index the library did not write) are ignored, never dereferenced.
+ *   fsmidx_restrict_rows / _fill write the index with the rows of all states q with keep[q] == 0
+ * left empty (keep = reach_out, or any other choice): state ids keep their meaning, the kept rows
+ * are unchanged and lie side by side in state order.  restrict_rows fills row_ptr_out_dev
+ * [n_states + 1] and returns the number of entries kept (one synchronisation); restrict_fill copies
+ * them into token_ids_out / next_states_out, which hold `capacity` >= that number of entries
+ * (asynchronous; a row that would not fit is not written).  {row_ptr_out, the new arrays} is an
+ * fsmidx_csr for mask_logits, advance_states and the masked choices; a generation that starts in a
+ * start state never meets a missing row.
+ *   `workspace`: device, 256-byte aligned, fsmidx_reach_workspace_bytes(n_states) bytes.
+ * n_states <= 2^26.
+ */
+int fsmidx_reach_workspace_bytes(int32_t n_states, size_t *bytes);
+int fsmidx_reachable_states(const fsmidx_csr *index, const int32_t *start_states_host, int32_t n_starts,
+                            void *workspace, size_t workspace_bytes, uint8_t *reach_out_dev /* [n_states] */,
+                            int32_t *n_reached_host, void *stream);
+int fsmidx_restrict_rows(const fsmidx_csr *index, const uint8_t *keep_dev /* [n_states] */, void *workspace,
+                         size_t workspace_bytes, int64_t *row_ptr_out_dev /* [n_states + 1] */, int64_t *nnz_out_host,
+                         void *stream);
+int fsmidx_restrict_fill(const fsmidx_csr *index, const uint8_t *keep_dev, const int64_t *row_ptr_out_dev,
+                         int32_t *token_ids_out_dev, int32_t *next_states_out_dev, int64_t capacity, void *stream);
+
+/*
  * Kernel timing for benchmarks.  After fsmidx_profile_enable(1) the calling thread's build,
  * mask_logits, advance_states, masked_argmax and masked_sample calls bracket each phase's kernels
  * with HIP events on the stream they are given (enable(0) stops that; either call resets the

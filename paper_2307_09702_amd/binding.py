@@ -27,6 +27,7 @@ EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "f
            "fsmidx_masked_sample_workspace_bytes", "fsmidx_masked_sample",
            "fsmidx_union_workspace_bytes", "fsmidx_union_dfa",
            "fsmidx_dedupe_workspace_bytes", "fsmidx_dedupe_rows", "fsmidx_dedupe_fill",
+           "fsmidx_reach_workspace_bytes", "fsmidx_reachable_states", "fsmidx_restrict_rows", "fsmidx_restrict_fill",
            "fsmidx_profile_enable", "fsmidx_profile_read")
 
 
@@ -107,6 +108,11 @@ def load():
     lib.fsmidx_dedupe_rows.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_int32),
                                        POINTER(c_int64), c_void_p]
     lib.fsmidx_dedupe_fill.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.fsmidx_reach_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
+    lib.fsmidx_reachable_states.argtypes = [POINTER(CCsr), POINTER(c_int32), c_int32, c_void_p, c_size_t, c_void_p,
+                                            POINTER(c_int32), c_void_p]
+    lib.fsmidx_restrict_rows.argtypes = [POINTER(CCsr), c_void_p, c_void_p, c_size_t, c_void_p, POINTER(c_int64), c_void_p]
+    lib.fsmidx_restrict_fill.argtypes = [POINTER(CCsr), c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
     lib.fsmidx_profile_enable.argtypes = [ctypes.c_int]
     lib.fsmidx_profile_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64)]
     for name in EXPORTS:
@@ -280,6 +286,47 @@ def dedupe_rows(csr: CCsr, device="cuda:0", stream=None):
     torch.cuda.synchronize()
     del ws
     return row_of, urp[:int(n_unique.value) + 1], tok[:int(nnz_unique.value)], nxt[:int(nnz_unique.value)]
+
+
+def reachable_states(csr: CCsr, starts, device="cuda:0", stream=None):
+    """fsmidx_reachable_states on torch tensors.  Returns (reach uint8 [n_states] on the device,
+    number of reachable states)."""
+    import torch
+    dev = torch.device(device)
+    n_states = int(csr.n_states)
+    need = c_size_t()
+    _check(load().fsmidx_reach_workspace_bytes(n_states, byref(need)))
+    ws, ws_ptr = _aligned(int(need.value), dev)
+    reach = torch.empty(n_states, dtype=torch.uint8, device=dev)
+    starts = [int(s) for s in starts]
+    arr = (c_int32 * max(len(starts), 1))(*starts)
+    n_reached = c_int32()
+    _check(load().fsmidx_reachable_states(byref(csr), arr, len(starts), ws_ptr, int(need.value), reach.data_ptr(),
+                                          byref(n_reached), _stream_handle(stream)))
+    del ws
+    return reach, int(n_reached.value)
+
+
+def restrict_rows(csr: CCsr, keep, device="cuda:0", stream=None):
+    """fsmidx_restrict_rows + fsmidx_restrict_fill on torch tensors (``keep``: uint8 [n_states] on
+    the device).  Returns (row_ptr int64 [n_states + 1], token_ids, next_states)."""
+    import torch
+    dev = torch.device(device)
+    n_states = int(csr.n_states)
+    need = c_size_t()
+    _check(load().fsmidx_reach_workspace_bytes(n_states, byref(need)))
+    ws, ws_ptr = _aligned(int(need.value), dev)
+    row_ptr = torch.empty(n_states + 1, dtype=torch.int64, device=dev)
+    nnz = c_int64()
+    _check(load().fsmidx_restrict_rows(byref(csr), keep.data_ptr(), ws_ptr, int(need.value), row_ptr.data_ptr(),
+                                       byref(nnz), _stream_handle(stream)))
+    tok = torch.empty(max(int(nnz.value), 1), dtype=torch.int32, device=dev)
+    nxt = torch.empty(max(int(nnz.value), 1), dtype=torch.int32, device=dev)
+    _check(load().fsmidx_restrict_fill(byref(csr), keep.data_ptr(), row_ptr.data_ptr(), tok.data_ptr(), nxt.data_ptr(),
+                                       int(nnz.value), _stream_handle(stream)))
+    torch.cuda.synchronize()
+    del ws
+    return row_ptr, tok[:int(nnz.value)], nxt[:int(nnz.value)]
 
 
 class DeviceProblem:

@@ -882,6 +882,108 @@ int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t wo
     return FSMIDX_OK;
 }
 
+int fsmidx_reach_workspace_bytes(int32_t n_states, size_t *bytes)
+{
+    if (!bytes)
+        return fail(FSMIDX_INVALID_ARG, "bytes must not be NULL");
+    if (n_states < 1 || n_states > kDedupeMaxStates)
+        return fail(FSMIDX_INVALID_ARG, "n_states must be in [1, %d]", kDedupeMaxStates);
+    *bytes = reach_workspace_bytes(n_states);
+    return FSMIDX_OK;
+}
+
+static int check_reach_workspace(const fsmidx_csr *index, const void *workspace, size_t workspace_bytes)
+{
+    if (int rc = check_rows(index))
+        return rc;
+    size_t need = 0;
+    if (int rc = fsmidx_reach_workspace_bytes(index->n_states, &need))
+        return rc;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return fail(FSMIDX_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    return FSMIDX_OK;
+}
+
+int fsmidx_reachable_states(const fsmidx_csr *index, const int32_t *start_states_host, int32_t n_starts, void *workspace,
+                            size_t workspace_bytes, uint8_t *reach_out_dev, int32_t *n_reached_host, void *stream_v)
+{
+    if (int rc = check_reach_workspace(index, workspace, workspace_bytes))
+        return rc;
+    if (!reach_out_dev || !n_reached_host)
+        return fail(FSMIDX_INVALID_ARG, "reach_out and n_reached_host must not be NULL");
+    if (n_starts < 0 || n_starts > index->n_states || (n_starts > 0 && !start_states_host))
+        return fail(FSMIDX_INVALID_ARG, "n_starts must be in [0, n_states] and start_states must not be NULL");
+    for (int32_t i = 0; i < n_starts; ++i)
+        if (start_states_host[i] < 0 || start_states_host[i] >= index->n_states)
+            return fail(FSMIDX_INVALID_ARG, "start state %d lies outside [0, %d)", start_states_host[i], index->n_states);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    FSMIDX_HIP(launch_reach_start(*index, ws, start_states_host, n_starts, stream));
+    // A level is one launch that reads its frontier's length from memory, so several are enqueued
+    // before the host looks whether the search has ended (a level with an empty frontier does
+    // nothing, and neither does any level after it): 8 at first, then twice as many each time, 64
+    // at most.  Every level but the last reaches a new state, so n_states levels are always enough.
+    int batch = 8;
+    uint32_t level = 0, pending = (uint32_t)n_starts;
+    for (;;) {
+        FSMIDX_HIP(launch_reach_levels(*index, ws, level, batch, pending, stream));
+        level += (uint32_t)batch;
+        FSMIDX_HIP(hipMemcpyAsync(&pending, reach_next_count(ws, index->n_states, level), 4, hipMemcpyDeviceToHost, stream));
+        FSMIDX_HIP(hipStreamSynchronize(stream));
+        if (pending == 0)
+            break;
+        if (level > (uint32_t)index->n_states + 64u)
+            return fail(FSMIDX_HIP_ERROR, "the search for reachable states did not end");
+        if (batch < 64)
+            batch *= 2;
+    }
+    FSMIDX_HIP(launch_reach_finish(*index, ws, reach_out_dev, stream));
+    int64_t reached = 0;
+    FSMIDX_HIP(hipMemcpyAsync(&reached, ws, 8, hipMemcpyDeviceToHost, stream));
+    FSMIDX_HIP(hipStreamSynchronize(stream));
+    *n_reached_host = (int32_t)reached;
+    return FSMIDX_OK;
+}
+
+int fsmidx_restrict_rows(const fsmidx_csr *index, const uint8_t *keep_dev, void *workspace, size_t workspace_bytes,
+                         int64_t *row_ptr_out_dev, int64_t *nnz_out_host, void *stream_v)
+{
+    if (int rc = check_reach_workspace(index, workspace, workspace_bytes))
+        return rc;
+    if (!keep_dev || !row_ptr_out_dev || !nnz_out_host)
+        return fail(FSMIDX_INVALID_ARG, "keep, row_ptr_out and nnz_out_host must not be NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    FSMIDX_HIP(launch_restrict_scan(*index, keep_dev, ws, row_ptr_out_dev, stream));
+    int64_t result[2] = {0, 0};
+    FSMIDX_HIP(hipMemcpyAsync(result, ws, sizeof(result), hipMemcpyDeviceToHost, stream));
+    FSMIDX_HIP(hipStreamSynchronize(stream));
+    *nnz_out_host = result[1];
+    return FSMIDX_OK;
+}
+
+int fsmidx_restrict_fill(const fsmidx_csr *index, const uint8_t *keep_dev, const int64_t *row_ptr_out_dev,
+                         int32_t *token_ids_out_dev, int32_t *next_states_out_dev, int64_t capacity, void *stream_v)
+{
+    if (int rc = check_rows(index))
+        return rc;
+    if (!keep_dev || !row_ptr_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "keep and row_ptr_out must not be NULL");
+    if (capacity < 0)
+        return fail(FSMIDX_INVALID_ARG, "capacity must not be negative");
+    if (index->nnz == 0 || capacity == 0)
+        return FSMIDX_OK;
+    if (!token_ids_out_dev || !next_states_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "token_ids_out and next_states_out must not be NULL when there are entries to copy");
+    if (index->n_states > kDedupeMaxStates)
+        return fail(FSMIDX_INVALID_ARG, "n_states must be at most %d", kDedupeMaxStates);
+    FSMIDX_HIP(launch_restrict_copy(*index, keep_dev, row_ptr_out_dev, token_ids_out_dev, next_states_out_dev, capacity,
+                                    static_cast<hipStream_t>(stream_v)));
+    return FSMIDX_OK;
+}
+
 int fsmidx_masked_sample_workspace_bytes(int32_t batch, size_t *bytes)
 {
     if (!bytes)

@@ -166,6 +166,18 @@ hipError_t launch_union_table(const fsmidx_dfa *dfas, int32_t n_dfas, const int3
                               int32_t n_union_classes, int32_t *trans_out, uint8_t *accept_out, char *ws,
                               hipStream_t stream);
 // identical rows; ws starts with int64 [3]: distinct rows, their entries, collision flag
+// reachable states of an index and the index restricted to a set of states (reach.hip)
+size_t reach_workspace_bytes(int32_t n_states);
+hipError_t launch_reach_start(const fsmidx_csr &csr, char *ws, const int32_t *starts_host, int32_t n_starts,
+                              hipStream_t stream);
+hipError_t launch_reach_levels(const fsmidx_csr &csr, char *ws, uint32_t first_level, int n_levels, uint32_t expected,
+                               hipStream_t stream);
+const uint32_t *reach_next_count(char *ws, int32_t n_states, uint32_t level);
+hipError_t launch_reach_finish(const fsmidx_csr &csr, char *ws, uint8_t *reach_out, hipStream_t stream);
+hipError_t launch_restrict_scan(const fsmidx_csr &csr, const uint8_t *keep, char *ws, int64_t *row_ptr_out,
+                                hipStream_t stream);
+hipError_t launch_restrict_copy(const fsmidx_csr &csr, const uint8_t *keep, const int64_t *row_ptr_out,
+                                int32_t *token_ids_out, int32_t *next_states_out, int64_t capacity, hipStream_t stream);
 size_t dedupe_workspace_bytes(int32_t n_states);
 hipError_t launch_dedupe(const fsmidx_csr &csr, char *ws, uint64_t seed, int32_t *row_of_state,
                          int64_t *unique_row_ptr, hipStream_t stream);
