@@ -215,7 +215,27 @@ def reduce_block(B, W, torch, dev, csr_large, n_states_large, nnz_large):
     csr_s, tok_s, nxt_s = prob_s.build()
     reach_some = reachable(csr_s, large.dfa.start)
     reach_some["vocabulary"] = "C3-large's tokens without the one-letter and one-digit ones (%d tokens)" % some.n_tokens
+    # minimisation before indexing (Section 5): the union of the eight automata (states that read
+    # the same continuations in different automata fall together), and one automaton un-reduced
+    def minimised(trans, b2c, accept, dead, n=5):
+        m = B.DeviceMinimised(trans, b2c, accept, dead)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            m = B.DeviceMinimised(trans, b2c, accept, dead)
+        torch.cuda.synchronize()
+        call_ms = (time.perf_counter() - t0) / n * 1e3
+        pm = B.DeviceProblem(m.trans, m.byte_to_class, m.accept, m.dead_state, vocab.bytes, vocab.offsets, -1)
+        return m, {"states": int(trans.shape[0]), "classes_of_equivalent_states": m.n_states, "entries_after": pm.count(),
+                   "call_ms_host_clock": call_ms}
+    _, min_union = minimised(u.trans, u.byte_to_class, u.accept, u.dead_state)
+    min_union["entries_before"] = union_nnz
+    raw = compile_regex(W.json_schema_regex(np.random.default_rng([2, 0]), 8, nested=False), minimise=False)
+    _, min_raw = minimised(raw.trans, raw.byte_to_class, raw.accept, raw.dead)
+    min_raw["entries_before"] = B.DeviceProblem(raw.trans, raw.byte_to_class, raw.accept, raw.dead, vocab.bytes,
+                                                vocab.offsets, -1).count()
     return {
+        "minimise": {"union_of_eight": min_union, "one_schema_automaton_as_the_subset_construction_leaves_it": min_raw},
         "reachable_only": {"C3-large": reach_large, "C3-large, no one-character alphanumeric tokens": reach_some},
         "union": {"automata": 8, "states": u.n_states, "classes": u.n_classes, "vocabulary": vocab.n_tokens,
                   "pairs": u.n_states * vocab.n_tokens, "nnz": union_nnz, "fsmidx_union_dfa_ms_host_clock": union_call_ms,

@@ -340,6 +340,34 @@ int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t wo
                        void *stream);
 
 /*
+ * Minimisation before indexing (Section 5: the paper's indices come from un-reduced automata, whose
+ * redundant states make them larger than they have to be).  What the index records about a walk is
+ * whether it meets the rejecting state and whether the state it ends in accepts (Section 3,
+ * Algorithms 3 and 4; Section 2.1 for EOS), so every state has one of three labels -- rejecting
+ * state, accepting, neither -- and two states are equivalent iff every string of byte classes leads
+ * them to equally labelled states.  A state from which nothing can be accepted any more is NOT the
+ * rejecting state: only `dead_state` rejects.  fsmidx_minimise_dfa finds the classes by refinement
+ * (exact: signatures are grouped by hash, then compared) and writes
+ *     block_of_state[q] = the class of q; classes are numbered in order of their smallest state
+ *     the quotient automaton: one state per class (trans_out [classes x n_classes], accept_out
+ *     [classes], the class of the rejecting state as its dead_state), described by *min_out, whose
+ *     byte_to_class is the input's pointer.
+ * The index of the quotient is the original's with state ids mapped through block_of_state: row q
+ * of the original holds the tokens of row block_of_state[q] of the quotient, and each end state s
+ * appears there as block_of_state[s].
+ *   `dfa`: DEVICE pointers, as for fsmidx_build_count; its table is range checked on the device
+ * (FSMIDX_BAD_DEVICE_INPUT).  Outputs are DEVICE memory of the caller: block_of_state [n_states],
+ * trans_out [trans_capacity] (n_states x n_classes always suffices; FSMIDX_OUTPUT_TOO_SMALL says
+ * how much is needed), accept_out [n_states].  `workspace`: device, 256-byte aligned,
+ * fsmidx_minimise_workspace_bytes(n_states) bytes.  The stream is synchronised once per 8 to 64
+ * rounds of refinement and once at the end.  n_states <= 2^26.
+ */
+int fsmidx_minimise_workspace_bytes(int32_t n_states, size_t *bytes);
+int fsmidx_minimise_dfa(const fsmidx_dfa *dfa, void *workspace, size_t workspace_bytes,
+                        int32_t *block_of_state_dev /* [n_states] */, int32_t *trans_out_dev, int64_t trans_capacity,
+                        uint8_t *accept_out_dev /* [n_states] */, fsmidx_dfa *min_out, void *stream);
+
+/*
  * The reachable-only index (Section 3, the paragraph after Algorithm 4: the index needs a row per
  * state in principle, but not every state is ever represented by a vocabulary string; Section 2.2,
  * Algorithm 2: a generation starts in q_0 and moves to the end state stored with each sampled

@@ -27,6 +27,7 @@ EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "f
            "fsmidx_masked_sample_workspace_bytes", "fsmidx_masked_sample",
            "fsmidx_union_workspace_bytes", "fsmidx_union_dfa",
            "fsmidx_dedupe_workspace_bytes", "fsmidx_dedupe_rows", "fsmidx_dedupe_fill",
+           "fsmidx_minimise_workspace_bytes", "fsmidx_minimise_dfa",
            "fsmidx_reach_workspace_bytes", "fsmidx_reachable_states", "fsmidx_restrict_rows", "fsmidx_restrict_fill",
            "fsmidx_profile_enable", "fsmidx_profile_read")
 
@@ -108,6 +109,9 @@ def load():
     lib.fsmidx_dedupe_rows.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_int32),
                                        POINTER(c_int64), c_void_p]
     lib.fsmidx_dedupe_fill.argtypes = [POINTER(CCsr), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.fsmidx_minimise_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
+    lib.fsmidx_minimise_dfa.argtypes = [POINTER(CDfa), c_void_p, c_size_t, c_void_p, c_void_p, c_int64, c_void_p,
+                                        POINTER(CDfa), c_void_p]
     lib.fsmidx_reach_workspace_bytes.argtypes = [c_int32, POINTER(c_size_t)]
     lib.fsmidx_reachable_states.argtypes = [POINTER(CCsr), POINTER(c_int32), c_int32, c_void_p, c_size_t, c_void_p,
                                             POINTER(c_int32), c_void_p]
@@ -263,6 +267,37 @@ class DeviceUnion:
         self.n_states, self.n_classes, self.dead_state = int(out.n_states), int(out.n_classes), int(out.dead_state)
         self.trans = self.trans_full[:self.n_states * self.n_classes].view(self.n_states, self.n_classes)
         self.state_base = np.array(list(base), dtype=np.int64)
+
+
+class DeviceMinimised:
+    """fsmidx_minimise_dfa: an automaton given as numpy arrays (or device tensors) is put on the
+    device and reduced there (device tensors ``trans`` [classes x n_classes], ``byte_to_class``,
+    ``accept``, ``block_of_state`` [states of the input]; ``n_states`` = number of classes)."""
+
+    def __init__(self, trans, byte_to_class, accept, dead_state, device="cuda:0", trans_capacity=None, stream=None):
+        import torch
+        self.device = torch.device(device)
+        to = lambda a, dt: a if hasattr(a, "data_ptr") and not isinstance(a, np.ndarray) else \
+            torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=dt))).to(self.device)
+        self._in = (to(trans, np.int32), to(byte_to_class, np.uint8), to(accept, np.uint8))
+        n_states, n_classes = int(self._in[0].shape[0]), int(self._in[0].shape[1])
+        if trans_capacity is None:
+            trans_capacity = n_states * n_classes
+        self.trans_full = torch.empty(max(trans_capacity, 1), dtype=torch.int32, device=self.device)
+        self.accept = torch.empty(n_states, dtype=torch.uint8, device=self.device)
+        self.block_of_state = torch.empty(n_states, dtype=torch.int32, device=self.device)
+        self.byte_to_class = self._in[1]
+        need = c_size_t()
+        _check(load().fsmidx_minimise_workspace_bytes(n_states, byref(need)))
+        ws, ws_ptr = _aligned(int(need.value), self.device)
+        src = CDfa(self._in[0].data_ptr(), n_states, n_classes, self._in[1].data_ptr(), self._in[2].data_ptr(), int(dead_state))
+        out = CDfa()
+        _check(load().fsmidx_minimise_dfa(byref(src), ws_ptr, int(need.value), self.block_of_state.data_ptr(),
+                                          self.trans_full.data_ptr(), int(trans_capacity), self.accept.data_ptr(),
+                                          byref(out), _stream_handle(stream)))
+        del ws
+        self.n_states, self.n_classes, self.dead_state = int(out.n_states), int(out.n_classes), int(out.dead_state)
+        self.trans = self.trans_full[:self.n_states * self.n_classes].view(self.n_states, self.n_classes)
 
 
 def dedupe_rows(csr: CCsr, device="cuda:0", stream=None):

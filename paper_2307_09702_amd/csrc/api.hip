@@ -882,6 +882,98 @@ int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t wo
     return FSMIDX_OK;
 }
 
+int fsmidx_minimise_workspace_bytes(int32_t n_states, size_t *bytes)
+{
+    if (!bytes)
+        return fail(FSMIDX_INVALID_ARG, "bytes must not be NULL");
+    if (n_states < 1 || n_states > kDedupeMaxStates)
+        return fail(FSMIDX_INVALID_ARG, "n_states must be in [1, %d]", kDedupeMaxStates);
+    *bytes = minimise_workspace_bytes(n_states);
+    return FSMIDX_OK;
+}
+
+int fsmidx_minimise_dfa(const fsmidx_dfa *dfa, void *workspace, size_t workspace_bytes, int32_t *block_of_state_dev,
+                        int32_t *trans_out_dev, int64_t trans_capacity, uint8_t *accept_out_dev, fsmidx_dfa *min_out,
+                        void *stream_v)
+{
+    if (!dfa || !min_out)
+        return fail(FSMIDX_INVALID_ARG, "dfa and min_out must not be NULL");
+    if (int rc = check_sizes(dfa->n_states, dfa->n_classes, 0, 0))
+        return rc;
+    size_t need = 0;
+    if (int rc = fsmidx_minimise_workspace_bytes(dfa->n_states, &need))
+        return rc;
+    if (!dfa->trans || !dfa->byte_to_class || !dfa->accept)
+        return fail(FSMIDX_INVALID_ARG, "dfa.trans, dfa.byte_to_class and dfa.accept must not be NULL");
+    if (dfa->dead_state < -1 || dfa->dead_state >= dfa->n_states)
+        return fail(FSMIDX_INVALID_ARG, "dead_state must be -1 or in [0, n_states) (got %d)", dfa->dead_state);
+    if (!block_of_state_dev || !trans_out_dev || !accept_out_dev || trans_capacity < 0)
+        return fail(FSMIDX_INVALID_ARG, "block_of_state, trans_out and accept_out must not be NULL");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return fail(FSMIDX_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < need)
+        return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    // Signatures are grouped by a 64-bit hash and then compared class by class; two different
+    // signatures with one hash make the whole refinement start again with another seed.
+    for (uint64_t attempt = 0; attempt < 4; ++attempt) {
+        const uint64_t seed = 0x452821E638D01377ull + attempt * 0x9E3779B97F4A7C15ull;
+        FSMIDX_HIP(launch_min_start(*dfa, ws, attempt == 0, stream));
+        // Rounds are enqueued in batches (8, 8, 16, 32, then 64 at a time); after each the host reads
+        // the class counts of its rounds.  The partition is final once a round leaves the count
+        // unchanged; rounds enqueued after that one change nothing.  Every round before splits a
+        // class, so n_states rounds are always enough.
+        int64_t classes = -1;
+        bool collided = false, done = false;
+        uint32_t round = 0;
+        int batch = 8;
+        while (!done && !collided) {
+            FSMIDX_HIP(launch_min_rounds(*dfa, ws, seed, round, batch, stream));
+            int64_t result[3] = {0, 0, 0};
+            uint32_t counts[64];
+            FSMIDX_HIP(hipMemcpyAsync(result, min_result(ws, dfa->n_states), sizeof(result), hipMemcpyDeviceToHost, stream));
+            FSMIDX_HIP(hipMemcpyAsync(counts, min_counts(ws, dfa->n_states) + round % (uint32_t)min_rounds_max(),
+                                      (size_t)batch * 4, hipMemcpyDeviceToHost, stream));
+            FSMIDX_HIP(hipStreamSynchronize(stream));
+            if (result[1])
+                return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text((uint32_t)result[1]),
+                            (uint32_t)result[1]);
+            collided = result[2] != 0;
+            for (int r = 0; r < batch && !done; ++r) {
+                done = (int64_t)counts[r] == classes;
+                classes = counts[r];
+            }
+            round += (uint32_t)batch;
+            if (round >= 16 && batch < 64)
+                batch *= 2;
+            if (!done && round > (uint32_t)dfa->n_states + 128u)
+                return fail(FSMIDX_HIP_ERROR, "the refinement did not end");
+        }
+        if (collided)
+            continue;
+        if (classes < 1 || classes > dfa->n_states)
+            return fail(FSMIDX_HIP_ERROR, "the class count came back as %lld", (long long)classes);
+        if (classes * dfa->n_classes > trans_capacity)
+            return fail(FSMIDX_OUTPUT_TOO_SMALL, "the quotient's table has %lld x %d entries, trans_out holds %lld",
+                        (long long)classes, dfa->n_classes, (long long)trans_capacity);
+        FSMIDX_HIP(launch_min_quotient(*dfa, ws, block_of_state_dev, trans_out_dev, trans_capacity, accept_out_dev, stream));
+        uint32_t dead_class = 0;
+        if (dfa->dead_state >= 0)
+            FSMIDX_HIP(hipMemcpyAsync(&dead_class, min_block(ws, dfa->n_states) + dfa->dead_state, 4, hipMemcpyDeviceToHost,
+                                      stream));
+        FSMIDX_HIP(hipStreamSynchronize(stream));
+        min_out->trans = trans_out_dev;
+        min_out->n_states = (int32_t)classes;
+        min_out->n_classes = dfa->n_classes;
+        min_out->byte_to_class = dfa->byte_to_class;
+        min_out->accept = accept_out_dev;
+        min_out->dead_state = dfa->dead_state >= 0 ? (int32_t)dead_class : -1;
+        return FSMIDX_OK;
+    }
+    return fail(FSMIDX_HIP_ERROR, "signature hashes collided four times in a row");
+}
+
 int fsmidx_reach_workspace_bytes(int32_t n_states, size_t *bytes)
 {
     if (!bytes)

@@ -166,6 +166,17 @@ hipError_t launch_union_table(const fsmidx_dfa *dfas, int32_t n_dfas, const int3
                               int32_t n_union_classes, int32_t *trans_out, uint8_t *accept_out, char *ws,
                               hipStream_t stream);
 // identical rows; ws starts with int64 [3]: distinct rows, their entries, collision flag
+// minimisation of an automaton (minimise.hip)
+size_t minimise_workspace_bytes(int32_t n_states);
+hipError_t launch_min_start(const fsmidx_dfa &dfa, char *ws, bool first_attempt, hipStream_t stream);
+hipError_t launch_min_rounds(const fsmidx_dfa &dfa, char *ws, uint64_t seed, uint32_t first_round, int n_rounds,
+                             hipStream_t stream);
+const int64_t *min_result(char *ws, int32_t n_states);
+const uint32_t *min_counts(char *ws, int32_t n_states);
+const uint32_t *min_block(char *ws, int32_t n_states);
+int min_rounds_max();
+hipError_t launch_min_quotient(const fsmidx_dfa &dfa, char *ws, int32_t *block_of_state, int32_t *trans_out,
+                               int64_t trans_capacity, uint8_t *accept_out, hipStream_t stream);
 // reachable states of an index and the index restricted to a set of states (reach.hip)
 size_t reach_workspace_bytes(int32_t n_states);
 hipError_t launch_reach_start(const fsmidx_csr &csr, char *ws, const int32_t *starts_host, int32_t n_starts,
