@@ -24,6 +24,9 @@ namespace fsmidx {
 
 constexpr int kReachSlices = 64;       // waves that share one row
 constexpr int kReachRecent = 64;       // end states a wave remembers having seen marked
+constexpr int kCopySlices = 16;        // waves that share one row when the kept rows are copied
+static_assert(kReachRecent == kWave, "every lane clears one entry of the table");
+static_assert((int64_t)kDedupeMaxStates * kCopySlices <= 0x7FFFFFFFll, "one workgroup per (state, slice) must fit a grid");
 constexpr int kReachGrid = 4096;       // most waves of one level's launch
 
 struct ReachBuffers {
@@ -75,9 +78,9 @@ __global__ __launch_bounds__(256) void reach_seed(const ReachBuffers b, int32_t 
 }
 
 // entries [i0, i1) of a row of n entries that belong to `slice`: whole multiples of a wave
-__device__ __forceinline__ void reach_slice(int64_t n, int32_t slice, int64_t &i0, int64_t &i1)
+__device__ __forceinline__ void reach_slice(int64_t n, int32_t slice, int32_t n_slices, int64_t &i0, int64_t &i1)
 {
-    int64_t per = (n + kReachSlices - 1) / kReachSlices;
+    int64_t per = (n + n_slices - 1) / n_slices;
     per = (per + kWave - 1) / kWave * kWave;
     i0 = min(n, (int64_t)slice * per);
     i1 = min(n, i0 + per);
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(kWave) void reach_level(const int64_t *__restrict__
         const int64_t lo = max((int64_t)0, min(row_ptr[q], nnz));
         const int64_t hi = max(lo, min(row_ptr[q + 1], nnz));
         int64_t i0, i1;
-        reach_slice(hi - lo, slice, i0, i1);
+        reach_slice(hi - lo, slice, kReachSlices, i0, i1);
         for (int64_t base = i0; base < i1; base += kWave) {
             const int64_t i = base + lane;
             bool won = false;
@@ -235,7 +238,7 @@ __global__ __launch_bounds__(1024) void restrict_scan(const int64_t *__restrict_
     }
 }
 
-// grid: n_states * kReachSlices
+// grid: n_states * kCopySlices
 __global__ __launch_bounds__(kWave) void restrict_copy(const int64_t *__restrict__ row_ptr,
                                                        const int32_t *__restrict__ token_ids,
                                                        const int32_t *__restrict__ next_states,
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(kWave) void restrict_copy(const int64_t *__restrict
                                                        int32_t *__restrict__ token_ids_out,
                                                        int32_t *__restrict__ next_states_out)
 {
-    const int32_t q = blockIdx.x / kReachSlices, slice = blockIdx.x % kReachSlices;
+    const int32_t q = blockIdx.x / kCopySlices, slice = blockIdx.x % kCopySlices;
     if (keep[q] == 0)
         return;
     const int64_t lo = max((int64_t)0, min(row_ptr[q], nnz));
@@ -253,7 +256,7 @@ __global__ __launch_bounds__(kWave) void restrict_copy(const int64_t *__restrict
     if (out < 0 || out > capacity - n)
         return;                                                    // (row_ptr_out is the caller's memory too)
     int64_t i0, i1;
-    reach_slice(n, slice, i0, i1);
+    reach_slice(n, slice, kCopySlices, i0, i1);
     for (int64_t i = i0 + threadIdx.x; i < i1; i += kWave) {
         token_ids_out[out + i] = token_ids[lo + i];
         next_states_out[out + i] = next_states[lo + i];
@@ -271,7 +274,7 @@ hipError_t launch_restrict_scan(const fsmidx_csr &csr, const uint8_t *keep, char
 hipError_t launch_restrict_copy(const fsmidx_csr &csr, const uint8_t *keep, const int64_t *row_ptr_out,
                                 int32_t *token_ids_out, int32_t *next_states_out, int64_t capacity, hipStream_t stream)
 {
-    hipLaunchKernelGGL(restrict_copy, dim3((unsigned)csr.n_states * kReachSlices), dim3(kWave), 0, stream, csr.row_ptr,
+    hipLaunchKernelGGL(restrict_copy, dim3((unsigned)csr.n_states * kCopySlices), dim3(kWave), 0, stream, csr.row_ptr,
                        csr.token_ids, csr.next_states, keep, csr.nnz, row_ptr_out, capacity, token_ids_out,
                        next_states_out);
     return hipGetLastError();
