@@ -2,9 +2,10 @@
 
 One step = one pass of the whole hot path over synthetic inputs that are already resident in
 HBM: build_index for the large JSON-schema automaton against the 128,256-token vocabulary
-(byte classification, table preparation, counting walk, scans, emitting walk: fsmidx_build_into,
-one stream synchronisation at its end) followed by
-mask_logits over a [256 x 128,256] batch in binary32 and in bfloat16.  The decode-step calls
+(byte classification, table preparation, counting walk, scans, emitting walk: fsmidx_build_enqueue)
+followed on the same stream by mask_logits over a [256 x 128,256] batch in binary32 and in
+bfloat16, and one stream synchronisation at the end of the step (fsmidx_build_finish, which reads
+the build's status).  The decode-step calls
 next to the mask (masked_argmax, masked_sample, advance_states) are timed on their own and reported beside the
 step.  Prints ONE JSON line.
 
@@ -324,10 +325,15 @@ def main():
     batch, n_vocab = logits_np.shape
 
     def step(i):
-        # the whole build in one call (the arrays are known to be large enough from the first build)
-        prob.build_into(token_ids, next_states)
+        # the whole build enqueued at once (the arrays are known to be large enough from the first
+        # build), the two masks that use the index behind it on the same stream, and one wait at the
+        # end of the step: build_finish reads the build's status there and would say so if the
+        # counting pass had to be redone (then the masks would have to be enqueued again: not here)
+        prob.build_enqueue(token_ids, next_states)
         B.mask_logits(csr, states, logits32[i % n_rot])
         B.mask_logits(csr, states, logits16[i % n_rot])
+        got, redone = prob.build_finish(token_ids, next_states)
+        assert got == nnz and not redone
 
     for i in range(args.warmup):
         step(i)

@@ -171,6 +171,30 @@ int fsmidx_build_into(const fsmidx_dfa *dfa_dev, const fsmidx_vocab *vocab_dev,
                       int64_t *nnz_host, void *stream);
 
 /*
+ * fsmidx_build_into in two halves, for a caller that has more work for the stream before it wants
+ * to wait (the masks of a decode batch that use the index, Section 2.2; the next build).
+ * fsmidx_build_enqueue launches the counting pass, the scans and the emitting pass (Section 3,
+ * Algorithms 3 and 4) and returns without waiting: it synchronises nothing, copies nothing and
+ * allocates nothing.  Work enqueued on the same stream after it sees the finished index -- row_ptr,
+ * the two arrays and the bitmap form in the workspace -- unless the build has to be repeated, which
+ * only fsmidx_build_finish can find out: it waits for the stream, reads the status and returns
+ * what fsmidx_build_into returns (same arguments, same error codes, *nnz_host).  If the counting
+ * pass had to be redone (an automaton that branches deeper than the first attempt's stack holds, or
+ * a build whose launch sequence followed a hint that no longer applies) it does that, waits again
+ * and sets *redone_host = 1 (else 0; may be NULL): whatever was enqueued between the two calls has
+ * then read an unfinished index and has to be enqueued again.  Input errors found on the device
+ * are reported by fsmidx_build_finish as well.  Both calls take the same arguments; the workspace
+ * and the inputs must not change in between.
+ */
+int fsmidx_build_enqueue(const fsmidx_dfa *dfa_dev, const fsmidx_vocab *vocab_dev,
+                         void *workspace, size_t workspace_bytes, int64_t *row_ptr_dev /* [n_states + 1] */,
+                         int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity, void *stream);
+int fsmidx_build_finish(const fsmidx_dfa *dfa_dev, const fsmidx_vocab *vocab_dev,
+                        void *workspace, size_t workspace_bytes, int64_t *row_ptr_dev,
+                        int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity,
+                        int64_t *nnz_host, int32_t *redone_host, void *stream);
+
+/*
  * Where fsmidx_build_count left the bitmap form of the index inside `workspace` (for the
  * allow_bits / allow_stride members of fsmidx_csr).  Valid from the return of fsmidx_build_count
  * until the workspace is written again; touches no GPU.

@@ -22,7 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "fsmidx_index_csr",
            "fsmidx_index_to_host", "fsmidx_free_index", "fsmidx_build_workspace_bytes",
-           "fsmidx_build_count", "fsmidx_build_fill", "fsmidx_build_into", "fsmidx_build_allow_bits", "fsmidx_mask_logits",
+           "fsmidx_build_count", "fsmidx_build_fill", "fsmidx_build_into", "fsmidx_build_enqueue", "fsmidx_build_finish", "fsmidx_build_allow_bits", "fsmidx_mask_logits",
            "fsmidx_advance_states", "fsmidx_masked_argmax_workspace_bytes", "fsmidx_masked_argmax", "fsmidx_masked_argmax_static",
            "fsmidx_masked_sample_workspace_bytes", "fsmidx_masked_sample",
            "fsmidx_union_workspace_bytes", "fsmidx_union_dfa",
@@ -89,6 +89,10 @@ def load():
                                       c_void_p, c_void_p, c_void_p]
     lib.fsmidx_build_into.argtypes = [POINTER(CDfa), POINTER(CVocab), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p,
                                       c_int64, POINTER(c_int64), c_void_p]
+    lib.fsmidx_build_enqueue.argtypes = [POINTER(CDfa), POINTER(CVocab), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p,
+                                         c_int64, c_void_p]
+    lib.fsmidx_build_finish.argtypes = [POINTER(CDfa), POINTER(CVocab), c_void_p, c_size_t, c_void_p, c_void_p, c_void_p,
+                                        c_int64, POINTER(c_int64), POINTER(c_int32), c_void_p]
     lib.fsmidx_build_allow_bits.argtypes = [c_int32, c_int32, c_int32, c_int64, c_void_p, POINTER(c_void_p),
                                             POINTER(c_int64)]
     lib.fsmidx_mask_logits.argtypes = [POINTER(CCsr), c_void_p, c_int32, c_void_p, c_void_p, c_int64, c_int32,
@@ -438,6 +442,29 @@ class DeviceProblem:
             raise err
         _check(rc)
         return int(nnz.value)
+
+    def build_enqueue(self, token_ids, next_states, stream=None) -> None:
+        """fsmidx_build_enqueue: the launches of build_into, without waiting for them."""
+        capacity = min(token_ids.numel(), next_states.numel())
+        _check(load().fsmidx_build_enqueue(byref(self.dfa_struct), byref(self.vocab_struct), self._ws_ptr,
+                                           self.workspace_bytes, self.row_ptr.data_ptr(),
+                                           _ptr(token_ids) if capacity else None, _ptr(next_states) if capacity else None,
+                                           capacity, _stream_handle(stream)))
+
+    def build_finish(self, token_ids, next_states, stream=None):
+        """fsmidx_build_finish: waits, returns (nnz, redone)."""
+        nnz, redone = c_int64(), c_int32()
+        capacity = min(token_ids.numel(), next_states.numel())
+        rc = load().fsmidx_build_finish(byref(self.dfa_struct), byref(self.vocab_struct), self._ws_ptr,
+                                        self.workspace_bytes, self.row_ptr.data_ptr(),
+                                        _ptr(token_ids) if capacity else None, _ptr(next_states) if capacity else None,
+                                        capacity, byref(nnz), byref(redone), _stream_handle(stream))
+        if rc == OUTPUT_TOO_SMALL:
+            err = OutputTooSmall(load().fsmidx_last_error().decode())
+            err.nnz = int(nnz.value)
+            raise err
+        _check(rc)
+        return int(nnz.value), bool(redone.value)
 
     def build(self, stream=None):
         """count + allocate + fill; returns (csr struct, token_ids tensor, next_states tensor)."""

@@ -482,18 +482,26 @@ int fsmidx_build_fill(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *wo
                         false, static_cast<hipStream_t>(stream_v));
 }
 
-int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *workspace, size_t workspace_bytes,
-                      int64_t *row_ptr_dev, int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity,
-                      int64_t *nnz_host, void *stream_v)
+static int check_build_outputs(const int64_t *row_ptr_dev, const int32_t *token_ids_dev, const int32_t *next_states_dev,
+                               int64_t capacity)
+{
+    if (!row_ptr_dev)
+        return fail(FSMIDX_INVALID_ARG, "row_ptr_dev must not be NULL");
+    if (capacity < 0 || (capacity > 0 && (!token_ids_dev || !next_states_dev)))
+        return fail(FSMIDX_INVALID_ARG, "capacity must be >= 0, and the two arrays must not be NULL when it is > 0");
+    return FSMIDX_OK;
+}
+
+int fsmidx_build_enqueue(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *workspace, size_t workspace_bytes,
+                         int64_t *row_ptr_dev, int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity,
+                         void *stream_v)
 {
     Plan p;
     int rc = plan_for(dfa, vocab, workspace, workspace_bytes, &p);
     if (rc)
         return rc;
-    if (!row_ptr_dev || !nnz_host)
-        return fail(FSMIDX_INVALID_ARG, "row_ptr_dev and nnz_host must not be NULL");
-    if (capacity < 0 || (capacity > 0 && (!token_ids_dev || !next_states_dev)))
-        return fail(FSMIDX_INVALID_ARG, "capacity must be >= 0, and the two arrays must not be NULL when it is > 0");
+    if ((rc = check_build_outputs(row_ptr_dev, token_ids_dev, next_states_dev, capacity)))
+        return rc;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char *ws = static_cast<char *>(workspace);
     rc = enqueue_count(p, dfa, vocab, ws, row_ptr_dev, stream);
@@ -501,16 +509,34 @@ int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *wo
         return rc;
     // the emit kernel itself checks, on the device, that the counting pass was clean and that the
     // entries fit; otherwise it writes nothing
-    if (capacity > 0) {
+    if (capacity > 0)
         rc = enqueue_emit(p, vocab, ws, row_ptr_dev, token_ids_dev, next_states_dev, capacity, true, stream);
-        if (rc)
-            return rc;
-    }
+    return rc;
+}
+
+int fsmidx_build_finish(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *workspace, size_t workspace_bytes,
+                        int64_t *row_ptr_dev, int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity,
+                        int64_t *nnz_host, int32_t *redone_host, void *stream_v)
+{
+    Plan p;
+    int rc = plan_for(dfa, vocab, workspace, workspace_bytes, &p);
+    if (rc)
+        return rc;
+    if ((rc = check_build_outputs(row_ptr_dev, token_ids_dev, next_states_dev, capacity)))
+        return rc;
+    if (!nnz_host)
+        return fail(FSMIDX_INVALID_ARG, "nnz_host must not be NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    if (redone_host)
+        *redone_host = 0;
     Status st;
     FSMIDX_HIP(read_status(ws, p, stream, &st));
     if (st.flags)
         return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(st.flags), st.flags);
     for (int attempt = 0; st.overflow && attempt < 2; ++attempt) {
+        if (redone_host)
+            *redone_host = 1;
         rc = enqueue_recount(p, dfa, vocab, ws, row_ptr_dev, attempt, st.overflow, stream);
         if (rc)
             return rc;
@@ -527,6 +553,20 @@ int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *wo
         return fail(FSMIDX_OUTPUT_TOO_SMALL, "the index has %lld entries, the arrays hold %lld", (long long)st.nnz,
                     (long long)capacity);
     return FSMIDX_OK;
+}
+
+int fsmidx_build_into(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *workspace, size_t workspace_bytes,
+                      int64_t *row_ptr_dev, int32_t *token_ids_dev, int32_t *next_states_dev, int64_t capacity,
+                      int64_t *nnz_host, void *stream_v)
+{
+    if (!nnz_host)
+        return fail(FSMIDX_INVALID_ARG, "row_ptr_dev and nnz_host must not be NULL");
+    int rc = fsmidx_build_enqueue(dfa, vocab, workspace, workspace_bytes, row_ptr_dev, token_ids_dev, next_states_dev,
+                                  capacity, stream_v);
+    if (rc)
+        return rc;
+    return fsmidx_build_finish(dfa, vocab, workspace, workspace_bytes, row_ptr_dev, token_ids_dev, next_states_dev,
+                               capacity, nnz_host, nullptr, stream_v);
 }
 
 int fsmidx_build_index(const fsmidx_dfa *dfa, const fsmidx_vocab *vocab, void *stream_v, fsmidx_index **out)

@@ -450,6 +450,57 @@ def test_single_call_build_when_the_search_stack_overflows(gpu, oracle_mod):
     assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok.cpu().numpy(), nxt.cpu().numpy(), "overflow, single call")
 
 
+def test_build_in_two_halves_with_masks_enqueued_in_between(gpu, oracle_mod):
+    """fsmidx_build_enqueue + fsmidx_build_finish: work enqueued between the two sees the finished
+    index; a build whose counting pass has to be redone says so."""
+    import torch
+    w = W.CONFIGS[2]()
+    d, v = w.dfa, w.vocab
+    ref = oracle_index(oracle_mod, d, v, 50256)
+    prob = gpu.DeviceProblem(d.trans, d.byte_to_class, d.accept, d.dead, v.bytes, v.offsets, 50256)
+    tok = torch.full((ref.nnz + 7,), -7, dtype=torch.int32, device="cuda")
+    nxt = torch.full((ref.nnz + 7,), -7, dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(2)
+    states = rng.integers(-1, d.n_states, size=16).astype(np.int32)
+    logits = (rng.standard_normal((16, v.n_tokens)) * 3).astype(np.float32)
+    want = oracle_mod.mask_logits(ref, v.n_tokens, states, logits)
+    st = torch.from_numpy(states).cuda()
+    for repeat in range(3):                                        # the first build has no hint, the later ones follow one
+        tok.fill_(-7); nxt.fill_(-7)
+        prob.row_ptr.fill_(-1)
+        x = torch.from_numpy(logits).cuda()
+        y = torch.from_numpy(logits).cuda()
+        torch.cuda.synchronize()
+        prob.build_enqueue(tok, nxt)
+        gpu.mask_logits(prob.csr(ref.nnz, tok, nxt), st, x)                         # bitmap form
+        gpu.mask_logits(prob.csr(ref.nnz, tok, nxt, with_bits=False), st, y)        # rows of the CSR
+        nnz, redone = prob.build_finish(tok, nxt)
+        torch.cuda.synchronize()
+        assert nnz == ref.nnz and not redone
+        assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok[:nnz].cpu().numpy(), nxt[:nnz].cpu().numpy(), "two halves")
+        assert bool((tok[nnz:] == -7).all())
+        assert x.cpu().numpy().tobytes() == want.tobytes() and y.cpu().numpy().tobytes() == want.tobytes()
+    # too small: finish reports the size needed
+    small = torch.full((ref.nnz - 1,), -7, dtype=torch.int32, device="cuda")
+    prob.build_enqueue(small, small.clone())
+    with pytest.raises(gpu.OutputTooSmall) as err:
+        prob.build_finish(small, small.clone())
+    assert err.value.nnz == ref.nnz
+    # a search that needs the deep stack: finish redoes the counting pass and says so
+    dfa = cyclic_dfa(12, (1, 2, 3))
+    toks = [bytes(rng.integers(0, 3, int(rng.integers(1, 25))).astype(np.uint8)) for _ in range(5000)]
+    vocab = W.Vocab.from_tokens(toks)
+    ref = oracle_index(oracle_mod, dfa, vocab)
+    prob = gpu.DeviceProblem(dfa.trans, dfa.byte_to_class, dfa.accept, dfa.dead, vocab.bytes, vocab.offsets, -1)
+    tok = torch.empty(ref.nnz, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(ref.nnz, dtype=torch.int32, device="cuda")
+    prob.build_enqueue(tok, nxt)
+    nnz, redone = prob.build_finish(tok, nxt)
+    torch.cuda.synchronize()
+    assert nnz == ref.nnz and redone
+    assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok.cpu().numpy(), nxt.cpu().numpy(), "two halves, redone")
+
+
 @pytest.mark.parametrize("longest", [3, 4, 5, 6, 7, 8, 9])
 def test_single_call_build_around_the_depths_of_both_search_stacks(gpu, oracle_mod, longest):
     """Three pairs per state and tokens of up to `longest` bytes need up to `longest` stack frames:
