@@ -225,3 +225,51 @@ def test_masked_sample_argument_checks(lib):
     for i in (1, 3, 6, 7, 9, 10):
         assert but(i, None) == B.INVALID_ARG
     assert lib.fsmidx_masked_sample(ctypes.byref(csr), None, 0, None, 1000, 0, None, None, 0, None, None, None) == B.OK
+
+
+def test_later_entry_points_reject_bad_arguments_before_any_launch(lib):
+    """build_enqueue / build_finish, minimise_dfa, reachable_states and restrict_rows / _fill check
+    sizes, pointers and workspaces on the host before anything touches the GPU."""
+    g = good()
+    d, v = B._structs(g["trans"], g["byte_to_class"], g["accept"], 4, g["vocab_bytes"], g["offsets"], -1)
+    need = B.build_workspace_bytes(5, 3, 5, 7)
+    args = (ctypes.byref(d), ctypes.byref(v))
+    nnz, redone = ctypes.c_int64(), ctypes.c_int32()
+    assert lib.fsmidx_build_enqueue(*args, 4096, need - 1, 4096, 4096, 4096, 10, None) == B.WORKSPACE_TOO_SMALL
+    assert lib.fsmidx_build_enqueue(*args, 4096, need, None, 4096, 4096, 10, None) == B.INVALID_ARG
+    assert lib.fsmidx_build_enqueue(*args, 4096, need, 4096, None, 4096, 10, None) == B.INVALID_ARG
+    assert lib.fsmidx_build_finish(*args, 4096, need, 4096, 4096, 4096, 10, None, ctypes.byref(redone), None) == B.INVALID_ARG
+    assert lib.fsmidx_build_finish(*args, 4096 + 8, need, 4096, 4096, 4096, 10, ctypes.byref(nnz), None, None) == B.INVALID_ARG
+    size = ctypes.c_size_t()
+    for fn in (lib.fsmidx_minimise_workspace_bytes, lib.fsmidx_reach_workspace_bytes):
+        assert fn(5036, ctypes.byref(size)) == B.OK and size.value % 256 == 0 and size.value >= 5036 * 12
+        assert fn(0, ctypes.byref(size)) == B.INVALID_ARG
+        assert fn(2 ** 26 + 1, ctypes.byref(size)) == B.INVALID_ARG
+        assert fn(5, None) == B.INVALID_ARG
+    lib.fsmidx_minimise_workspace_bytes(5, ctypes.byref(size))
+    out = B.CDfa()
+    mini = lambda dfa, ws, ws_bytes, blocks, trans, cap, acc, o: lib.fsmidx_minimise_dfa(dfa, ws, ws_bytes, blocks, trans, cap, acc, o, None)
+    assert mini(None, 4096, size.value, 4096, 4096, 15, 4096, ctypes.byref(out)) == B.INVALID_ARG
+    assert mini(ctypes.byref(d), 4096, size.value, 4096, 4096, 15, 4096, None) == B.INVALID_ARG
+    assert mini(ctypes.byref(d), 4096, size.value - 1, 4096, 4096, 15, 4096, ctypes.byref(out)) == B.WORKSPACE_TOO_SMALL
+    assert mini(ctypes.byref(d), 4096 + 16, size.value, 4096, 4096, 15, 4096, ctypes.byref(out)) == B.INVALID_ARG
+    assert mini(ctypes.byref(d), 4096, size.value, None, 4096, 15, 4096, ctypes.byref(out)) == B.INVALID_ARG
+    bad = B.CDfa(d.trans, d.n_states, d.n_classes, d.byte_to_class, d.accept, 9)
+    assert mini(ctypes.byref(bad), 4096, size.value, 4096, 4096, 15, 4096, ctypes.byref(out)) == B.INVALID_ARG
+    csr = B.CCsr(5, 5, 3, 4096, 4096, 4096, None, 0)
+    lib.fsmidx_reach_workspace_bytes(5, ctypes.byref(size))
+    starts = (ctypes.c_int32 * 2)(0, 5)
+    n = ctypes.c_int32()
+    reach = lambda index, st, n_st, ws, ws_bytes, out_dev, n_out: lib.fsmidx_reachable_states(index, st, n_st, ws, ws_bytes, out_dev, n_out, None)
+    assert reach(None, starts, 1, 4096, size.value, 4096, ctypes.byref(n)) == B.INVALID_ARG
+    assert reach(ctypes.byref(csr), starts, 2, 4096, size.value, 4096, ctypes.byref(n)) == B.INVALID_ARG      # state 5 of 5
+    assert b"start state" in lib.fsmidx_last_error()
+    assert reach(ctypes.byref(csr), starts, -1, 4096, size.value, 4096, ctypes.byref(n)) == B.INVALID_ARG
+    assert reach(ctypes.byref(csr), None, 1, 4096, size.value, 4096, ctypes.byref(n)) == B.INVALID_ARG
+    assert reach(ctypes.byref(csr), starts, 1, 4096, size.value - 1, 4096, ctypes.byref(n)) == B.WORKSPACE_TOO_SMALL
+    assert reach(ctypes.byref(csr), starts, 1, 4096, size.value, None, ctypes.byref(n)) == B.INVALID_ARG
+    assert lib.fsmidx_restrict_rows(ctypes.byref(csr), None, 4096, size.value, 4096, ctypes.byref(nnz), None) == B.INVALID_ARG
+    assert lib.fsmidx_restrict_rows(ctypes.byref(csr), 4096, 4096, size.value, 4096, None, None) == B.INVALID_ARG
+    assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, None, 4096, 4096, 3, None) == B.INVALID_ARG
+    assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, 4096, 4096, 4096, -1, None) == B.INVALID_ARG
+    assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, 4096, None, 4096, 3, None) == B.INVALID_ARG
