@@ -78,6 +78,7 @@ int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_b
     p->off_sync = o;   o = align256(o + sizeof(SyncWords));
     p->off_cls = o;    o = align256(o + (size_t)n_bytes + 16);
     p->off_tok = o;    o = align256(o + (size_t)p->n_chunks * kChunkTokens * sizeof(TokenRecord));
+    p->off_key = o;    o = align256(o + (size_t)p->n_chunks * kChunkTokens * 4);
     p->off_tab = o;    o = align256(o + (size_t)n_states * n_classes * p->entry_bytes + 16);
     p->off_live = o;   o = align256(o + (size_t)n_states * p->live_words * 8);
     p->off_cnt = o;    o = align256(o + (size_t)n_states * (size_t)p->n_groups * 4);

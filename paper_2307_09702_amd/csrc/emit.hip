@@ -68,7 +68,10 @@ struct EmitArgs {
 
 // LDS of one workgroup (= wave); the two ways of working never meet in one workgroup.
 union alignas(16) EmitShared {
-    uint16_t list[kEmitPart];                 // walking: token numbers of a part, rank order
+    struct {
+        uint16_t list[kEmitPart];             // walking: token numbers of a part, rank order
+        uint32_t row[256];                    //          row q of the table: the state after a token's first byte
+    } walk;
     struct {
         uint32_t node_state[kDirectNode + 1]; // searching: end state of every node
         uint32_t spread[16];                  //            byte i of entry x = bit i of x
@@ -88,62 +91,125 @@ struct SpanOut {
     int64_t base[kWalkBlocks];
 };
 
-// Ranks g0 + k * 64 + lane (k < K) of the list: load the token records, walk, store.
+// Ranks g0 + k * 64 + lane (k < K) of the list: walk the tokens, store.  Most admissible tokens
+// are short, so a token is first read in its four-byte form (the classes of its first three bytes
+// and its length: consecutive ranks are tokens a few ids apart, and their short forms share cache
+// lines where their 16-byte records do not); the first byte is looked up in row q, which is in
+// LDS; only a token of more than three bytes has its record fetched.
 template <typename E, int K>
 __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord *__restrict__ tok_b,
+                                           const uint32_t *__restrict__ key_b,
                                            const uint8_t *__restrict__ cls, const E *__restrict__ tab,
-                                           const uint16_t *list, const int32_t q, const int32_t token0, const int lane,
+                                           const uint16_t *list, const uint32_t *row_q, const int32_t q,
+                                           const int32_t token0, const int lane,
                                            const SpanOut &out, const uint32_t r0, const uint32_t g0, const uint32_t r1,
-                                           const uint32_t n_classes)
+                                           const uint32_t n_classes, const bool short_first)
 {
-    uint32_t t[K], s[K], len[K], off[K];
+    uint32_t t[K], s[K], len[K], kk[K];
+    uint32_t off[K];
     uint64_t pk[K];
-    uint32_t longest = 0;                                   // of this lane's walks
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
         t[k] = r < r1 ? (uint32_t)list[r - r0] : 0u;
     }
+    // (short_first is uniform; without it the record is read at once and the short form made from it)
+    if (short_first) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            kk[k] = key_b[t[k]];
+            pk[k] = 0;
+            off[k] = 0;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const TokenRecord rec = tok_b[t[k]];
+            pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+            off[k] = rec.offset;
+            kk[k] = (rec.cls_lo & 0xFFFFFFu) | (rec.length < 255u ? rec.length : 255u) << 24;
+            len[k] = rec.length;                            // (kept for the long ones below)
+        }
+    }
+    uint32_t real_len[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        real_len[k] = short_first ? 0u : len[k];
+    bool any_long = false;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
-        const TokenRecord rec = tok_b[t[k]];
-        pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
-        off[k] = rec.offset;
-        len[k] = r < r1 ? rec.length : 0u;
-        s[k] = (uint32_t)q;
-        longest = max(longest, len[k]);
+        len[k] = r < r1 ? kk[k] >> 24 : 0u;                 // (255: more than 254 bytes, see the record)
+        // (EOS and empty tokens have length 0: the end state is the state itself)
+        s[k] = len[k] != 0u ? row_q[kk[k] & 255u] : (uint32_t)q;
+        any_long = any_long || len[k] > 3u;
     }
-    // Bytes 0..7: classes from the record.  Every lane looks up in every step (a walk that is over
-    // reads entry 0, one cache line for all such lanes, and drops the result), so the K loads of a
-    // step are issued together and nothing branches on a lane.
+    // bytes 1 and 2: every lane looks up (a walk that is over reads entry 0, one cache line for all
+    // such lanes, and drops the result), so the K loads of a step are issued together
 #pragma unroll
-    for (int i = 0; i < kPackedClasses; ++i) {
-        if (__ballot((uint32_t)i < longest) == 0)
+    for (int i = 1; i < 3; ++i) {
+        bool some = false;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            some = some || len[k] > (uint32_t)i;
+        if (__ballot(some) == 0)
             break;
         uint32_t next[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
-            const uint32_t half = i < 4 ? (uint32_t)pk[k] : (uint32_t)(pk[k] >> 32);
-            const uint32_t c = (half >> (8 * (i & 3))) & 255u;
+            const uint32_t c = (kk[k] >> (8 * i)) & 255u;
             next[k] = (uint32_t)tab[(uint32_t)i < len[k] ? s[k] * n_classes + c : 0u];
         }
 #pragma unroll
         for (int k = 0; k < K; ++k)
             s[k] = (uint32_t)i < len[k] ? next[k] : s[k];
     }
-    // Bytes 8 and up (few tokens are that long): classes from the class string.
-    for (uint32_t i = (uint32_t)kPackedClasses; __ballot(i < longest) != 0; ++i) {
-        uint32_t c[K], next[K];
+    if (__ballot(any_long) != 0) {
+        // tokens of more than three bytes: their records (if not read yet), then bytes 3 .. 7 from
+        // the record and the rest from the class string
+        uint32_t longest = 0;
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            c[k] = i < len[k] ? (uint32_t)cls[off[k] + i] : 0u;
+        for (int k = 0; k < K; ++k) {
+            if (len[k] > 3u) {
+                if (short_first) {
+                    const TokenRecord rec = tok_b[t[k]];
+                    pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+                    off[k] = rec.offset;
+                    real_len[k] = rec.length;
+                }
+                len[k] = real_len[k];
+                longest = max(longest, len[k]);
+            } else {
+                len[k] = 0;                                 // finished
+            }
+        }
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            next[k] = (uint32_t)tab[i < len[k] ? s[k] * n_classes + c[k] : 0u];
+        for (int i = 3; i < kPackedClasses; ++i) {
+            if (__ballot((uint32_t)i < longest) == 0)
+                break;
+            uint32_t next[K];
 #pragma unroll
-        for (int k = 0; k < K; ++k)
-            s[k] = i < len[k] ? next[k] : s[k];
+            for (int k = 0; k < K; ++k) {
+                const uint32_t half = i < 4 ? (uint32_t)pk[k] : (uint32_t)(pk[k] >> 32);
+                const uint32_t c = (half >> (8 * (i & 3))) & 255u;
+                next[k] = (uint32_t)tab[(uint32_t)i < len[k] ? s[k] * n_classes + c : 0u];
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                s[k] = (uint32_t)i < len[k] ? next[k] : s[k];
+        }
+        for (uint32_t i = (uint32_t)kPackedClasses; __ballot(i < longest) != 0; ++i) {
+            uint32_t c[K], next[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                c[k] = i < len[k] ? (uint32_t)cls[off[k] + i] : 0u;
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                next[k] = (uint32_t)tab[i < len[k] ? s[k] * n_classes + c[k] : 0u];
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                s[k] = i < len[k] ? next[k] : s[k];
+        }
     }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -440,11 +506,21 @@ template <typename E>
 __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__restrict__ allow,
                                           const TokenRecord *__restrict__ tok,
                                           const uint8_t *__restrict__ cls, const E *__restrict__ tab,
+                                          const uint32_t *__restrict__ key,
                                           const int32_t q, const int32_t b0, const uint32_t part,
-                                          const uint32_t parts, const int lane, uint16_t *list)
+                                          const uint32_t parts, const int lane, uint16_t *list, uint32_t *row_q)
 {
     uint64_t A[kWalkBlocks];
     uint32_t own[kWalkBlocks], first[kWalkBlocks], n_w[kWalkBlocks];
+    // row q of the table, what the first byte of every token of the span is looked up in: loaded
+    // together with the admissibility words, put into LDS once the span is known to have entries
+    const uint32_t n_classes = (uint32_t)a.n_classes;
+    uint32_t row_ahead[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint32_t c = (uint32_t)(j * kWave + lane);
+        row_ahead[j] = (uint32_t)(j * kWave) < n_classes && c < n_classes ? (uint32_t)tab[(uint32_t)q * n_classes + c] : 0u;
+    }
 #pragma unroll
     for (int w = 0; w < kWalkBlocks; ++w) {
         A[w] = b0 + w < a.n_blocks ? allow[(int64_t)q * a.n_chunks + (int64_t)(b0 + w) * kBlockChunks + lane] : 0ull;
@@ -497,10 +573,20 @@ __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__r
     out.start[kWalkBlocks] = n;
     if (n == 0)
         return;
-    const uint32_t n_classes = (uint32_t)a.n_classes;
     const int32_t token0 = b0 * kBlockTokens;
     const TokenRecord *tok_b = tok + (size_t)token0;
+    const uint32_t *key_b = key + (size_t)token0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if ((uint32_t)(j * kWave) < n_classes)
+            row_q[j * kWave + lane] = row_ahead[j];
+    __builtin_amdgcn_wave_barrier();
 
+    // The short form of the tokens first where the texture addresser is what bounds the walk: a large
+    // automaton without structure, whose admissible tokens are mostly short.  Small problems are
+    // bound by their round trips, and the walked rows of JSON-like automata hold whole keys: there
+    // the record is read at once.
+    const bool short_first = !per_block && parts == 1u;
     // (small problems have few spans: then `parts` waves share a span, taking its parts of
     // kEmitPart ranks in turn)
     for (uint32_t r0 = part * (uint32_t)kEmitPart; r0 < n; r0 += parts * (uint32_t)kEmitPart) {
@@ -527,10 +613,11 @@ __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__r
         for (uint32_t g0 = r0; g0 < r1;) {
             const uint32_t left = r1 - g0;
             if (left > (uint32_t)kWave) {
-                walk_ranks<E, kEmitK>(a, tok_b, cls, tab, list, q, token0, lane, out, r0, g0, r1, n_classes);
+                walk_ranks<E, kEmitK>(a, tok_b, key_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes,
+                                      short_first);
                 g0 += (uint32_t)(kWave * kEmitK);
             } else {
-                walk_ranks<E, 1>(a, tok_b, cls, tab, list, q, token0, lane, out, r0, g0, r1, n_classes);
+                walk_ranks<E, 1>(a, tok_b, key_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes, short_first);
                 g0 += (uint32_t)kWave;
             }
         }
@@ -550,6 +637,7 @@ template <typename E>
 __global__ __launch_bounds__(kWave) void emit_csr(const EmitArgs a, const uint64_t *__restrict__ allow,
                                                   const TokenRecord *__restrict__ tok,
                                                   const uint8_t *__restrict__ cls, const E *__restrict__ tab,
+                                                  const uint32_t *__restrict__ key,
                                                   const StateRecord *__restrict__ srec,
                                                   const uint32_t *__restrict__ pairs, const uint64_t *__restrict__ U,
                                                   const uint64_t *__restrict__ Ebits)
@@ -574,7 +662,8 @@ __global__ __launch_bounds__(kWave) void emit_csr(const EmitArgs a, const uint64
         // token-set path: the states with several pairs first, as in the counting walk (their rows
         // are the long ones, and what starts last is what the kernel ends with)
         const uint32_t q = a.st->use_sets != 0 ? a.order[slot] : slot;
-        emit_span<E>(a, allow, tok, cls, tab, (int32_t)q, (int32_t)(span * kWalkBlocks), part, a.parts, lane, shared.list);
+        emit_span<E>(a, allow, tok, cls, tab, key, (int32_t)q, (int32_t)(span * kWalkBlocks), part, a.parts, lane,
+                     shared.walk.list, shared.walk.row);
     }
 }
 
@@ -603,6 +692,7 @@ hipError_t launch_emit(const Plan &p, const fsmidx_vocab &vocab, char *ws, const
     const int64_t items = (int64_t)p.n_states * p.n_blocks;
     a.n_long_groups = p.sets_possible ? (uint32_t)(items < kLongGrid ? items : kLongGrid) : 0u;
     const TokenRecord *tok = reinterpret_cast<const TokenRecord *>(ws + p.off_tok);
+    const uint32_t *key = reinterpret_cast<const uint32_t *>(ws + p.off_key);
     const uint8_t *cls = reinterpret_cast<const uint8_t *>(ws + p.off_cls);
     const StateRecord *srec = reinterpret_cast<const StateRecord *>(ws + p.off_srec);
     const uint32_t *pairs = reinterpret_cast<const uint32_t *>(ws + p.off_pairs);
@@ -620,10 +710,10 @@ hipError_t launch_emit(const Plan &p, const fsmidx_vocab &vocab, char *ws, const
         hipLaunchKernelGGL(reset_queues, dim3(1), dim3(kQueues), 0, stream, a.queue);
     if (p.entry_bytes == 2)
         hipLaunchKernelGGL(emit_csr<uint16_t>, grid, dim3(kWave), 0, stream, a, allow, tok, cls,
-                           reinterpret_cast<const uint16_t *>(ws + p.off_tab), srec, pairs, U, Ebits);
+                           reinterpret_cast<const uint16_t *>(ws + p.off_tab), key, srec, pairs, U, Ebits);
     else
         hipLaunchKernelGGL(emit_csr<uint32_t>, grid, dim3(kWave), 0, stream, a, allow, tok, cls,
-                           reinterpret_cast<const uint32_t *>(ws + p.off_tab), srec, pairs, U, Ebits);
+                           reinterpret_cast<const uint32_t *>(ws + p.off_tab), key, srec, pairs, U, Ebits);
     return hipGetLastError();
 }
 

@@ -85,6 +85,7 @@ struct Plan {
     size_t off_sync = 0;           // SyncWords
     size_t off_cls = 0;            // uint8  [n_bytes]            class of every vocabulary byte
     size_t off_tok = 0;            // TokenRecord [n_chunks * 64]
+    size_t off_key = 0;            // uint32 [n_chunks * 64] a token in four bytes: classes of its first three bytes, min(length, 255)
     size_t off_tab = 0;            // uint16/uint32 [n_states * n_classes]
     size_t off_live = 0;           // uint64 [n_states * live_words]
     size_t off_cnt = 0;            // uint32 [n_states * n_groups]  counts, then exclusive offsets

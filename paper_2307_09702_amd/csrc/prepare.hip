@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void classify_bytes(const uint8_t *__restrict_
 // The record of token slot t (slots past the last token get an empty record).
 __device__ __forceinline__ void pack_token(int32_t t, const int64_t *__restrict__ offsets, int32_t n_tokens,
                                            int64_t n_bytes, int32_t eos, int32_t n_slots,
-                                           const uint8_t *__restrict__ cls, TokenRecord *__restrict__ tok, Status *st)
+                                           const uint8_t *__restrict__ cls, TokenRecord *__restrict__ tok,
+                                           uint32_t *__restrict__ key, Status *st)
 {
     if (t >= n_slots)
         return;
@@ -111,6 +112,9 @@ __device__ __forceinline__ void pack_token(int32_t t, const int64_t *__restrict_
         }
     }
     tok[t] = r;
+    // the short form for the passes that mostly meet short tokens: three classes and the length in
+    // one word (a length of 255 says: look at the record)
+    key[t] = (r.cls_lo & 0xFFFFFFu) | (r.length < 255u ? r.length : 255u) << 24;
     // the token-set path handles tokens of up to kMaxSetDepth bytes (a plain store: every writer
     // writes the same value)
     if (r.length > (uint32_t)kMaxSetDepth)
@@ -401,6 +405,7 @@ template <typename E>
 __global__ __launch_bounds__(256) void pack_and_narrow(int32_t pack_groups, const int64_t *__restrict__ offsets,
                                                        int32_t n_tokens, int64_t n_bytes, int32_t eos, int32_t n_slots,
                                                        const uint8_t *__restrict__ cls, TokenRecord *__restrict__ tok,
+                                                       uint32_t *__restrict__ key,
                                                        const int32_t *__restrict__ trans, int32_t n_states,
                                                        int32_t n_classes, int32_t dead, int32_t live_words,
                                                        E *__restrict__ tab, uint64_t *__restrict__ live,
@@ -408,7 +413,7 @@ __global__ __launch_bounds__(256) void pack_and_narrow(int32_t pack_groups, cons
                                                        uint64_t *__restrict__ pmask, Status *st)
 {
     if ((int32_t)blockIdx.x < pack_groups) {
-        pack_token((int32_t)(blockIdx.x * blockDim.x + threadIdx.x), offsets, n_tokens, n_bytes, eos, n_slots, cls, tok, st);
+        pack_token((int32_t)(blockIdx.x * blockDim.x + threadIdx.x), offsets, n_tokens, n_bytes, eos, n_slots, cls, tok, key, st);
         return;
     }
     const int32_t q = ((int32_t)blockIdx.x - pack_groups) * 4 + (int32_t)(threadIdx.x >> 6);
@@ -424,6 +429,7 @@ hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_voc
     SyncWords *sy = reinterpret_cast<SyncWords *>(ws + p.off_sync);
     uint8_t *cls = reinterpret_cast<uint8_t *>(ws + p.off_cls);
     TokenRecord *tok = reinterpret_cast<TokenRecord *>(ws + p.off_tok);
+    uint32_t *key = reinterpret_cast<uint32_t *>(ws + p.off_key);
     uint64_t *live = reinterpret_cast<uint64_t *>(ws + p.off_live);
     const bool with_sets = p.sets_possible;
     uint32_t *npairs = with_sets ? reinterpret_cast<uint32_t *>(ws + p.off_npairs) : nullptr;
@@ -450,12 +456,12 @@ hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_voc
     const dim3 grid((unsigned)(pack_groups + (p.n_states + 3) / 4));
     if (p.entry_bytes == 2)
         hipLaunchKernelGGL(pack_and_narrow<uint16_t>, grid, dim3(256), 0, stream, pack_groups, vocab.offsets, p.n_tokens,
-                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, dfa.trans, p.n_states, p.n_classes,
+                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, key, dfa.trans, p.n_states, p.n_classes,
                            dfa.dead_state, p.live_words, reinterpret_cast<uint16_t *>(ws + p.off_tab), live, npairs, pairs,
                            pmask, st);
     else
         hipLaunchKernelGGL(pack_and_narrow<uint32_t>, grid, dim3(256), 0, stream, pack_groups, vocab.offsets, p.n_tokens,
-                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, dfa.trans, p.n_states, p.n_classes,
+                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, key, dfa.trans, p.n_states, p.n_classes,
                            dfa.dead_state, p.live_words, reinterpret_cast<uint32_t *>(ws + p.off_tab), live,
                            static_cast<uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), static_cast<uint64_t *>(nullptr), st);
     if (with_sets)
