@@ -44,6 +44,7 @@ constexpr int kDirectNode = (1 << kNodeBits) - 1;   // the number that says: sto
 constexpr int kFlush = 4 * kWave;      // entries of a searched segment that leave LDS together
 constexpr int kEmitPart = 1024;        // entries expanded into LDS at a time
 constexpr int kEmitK = 2;              // ranks per lane in flight
+constexpr int kDeferCap = 256;         // walks of more than two bytes put aside at a time (dense path)
 constexpr int kSpanTarget = 8192;      // walked spans (times parts) a launch should at least have
 constexpr int kMaxParts = 16;
 constexpr int kWalkBlocks = 4;         // consecutive blocks of a row that one wave walks (token numbers fit 16 bits)
@@ -71,6 +72,8 @@ union alignas(16) EmitShared {
     struct {
         uint16_t list[kEmitPart];             // walking: token numbers of a part, rank order
         uint32_t row[256];                    //          row q of the table: the state after a token's first byte
+        uint32_t later_state[kDeferCap];      //          walks put aside: state after two bytes ...
+        uint16_t later_rank[kDeferCap];       //          ... and rank within the part
     } walk;
     struct {
         uint32_t node_state[kDirectNode + 1]; // searching: end state of every node
@@ -91,19 +94,27 @@ struct SpanOut {
     int64_t base[kWalkBlocks];
 };
 
-// Ranks g0 + k * 64 + lane (k < K) of the list: walk the tokens, store.  Most admissible tokens
-// are short, so a token is first read in its four-byte form (the classes of its first three bytes
-// and its length: consecutive ranks are tokens a few ids apart, and their short forms share cache
-// lines where their 16-byte records do not); the first byte is looked up in row q, which is in
-// LDS; only a token of more than three bytes has its record fetched.
+// Where entry r of the span goes.
+__device__ __forceinline__ int64_t span_pos(const SpanOut &out, const uint32_t r)
+{
+    int64_t pos = out.base[0] + r;
+#pragma unroll
+    for (int w = 1; w < kWalkBlocks; ++w)
+        if (r >= out.start[w])
+            pos = out.base[w] + (r - out.start[w]);
+    return pos;
+}
+
+// Ranks g0 + k * 64 + lane (k < K) of the list: load the token records, walk, store.  The first
+// byte is looked up in row q, which is in LDS; the next two bytes are looked up by every lane, and
+// the bytes after them only if some token of the wave is that long.
 template <typename E, int K>
 __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord *__restrict__ tok_b,
-                                           const uint32_t *__restrict__ key_b,
                                            const uint8_t *__restrict__ cls, const E *__restrict__ tab,
                                            const uint16_t *list, const uint32_t *row_q, const int32_t q,
                                            const int32_t token0, const int lane,
                                            const SpanOut &out, const uint32_t r0, const uint32_t g0, const uint32_t r1,
-                                           const uint32_t n_classes, const bool short_first)
+                                           const uint32_t n_classes)
 {
     uint32_t t[K], s[K], len[K], kk[K];
     uint32_t off[K];
@@ -113,28 +124,20 @@ __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord 
         const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
         t[k] = r < r1 ? (uint32_t)list[r - r0] : 0u;
     }
-    // (short_first is uniform; without it the record is read at once and the short form made from it)
-    if (short_first) {
+    // the record, and from it the short form the first bytes are read from: the classes of the
+    // first three bytes and the length (255: 255 bytes or more)
 #pragma unroll
-        for (int k = 0; k < K; ++k) {
-            kk[k] = key_b[t[k]];
-            pk[k] = 0;
-            off[k] = 0;
-        }
-    } else {
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const TokenRecord rec = tok_b[t[k]];
-            pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
-            off[k] = rec.offset;
-            kk[k] = (rec.cls_lo & 0xFFFFFFu) | (rec.length < 255u ? rec.length : 255u) << 24;
-            len[k] = rec.length;                            // (kept for the long ones below)
-        }
+    for (int k = 0; k < K; ++k) {
+        const TokenRecord rec = tok_b[t[k]];
+        pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+        off[k] = rec.offset;
+        kk[k] = (rec.cls_lo & 0xFFFFFFu) | (rec.length < 255u ? rec.length : 255u) << 24;
+        len[k] = rec.length;                                // (kept for the long ones below)
     }
     uint32_t real_len[K];
 #pragma unroll
     for (int k = 0; k < K; ++k)
-        real_len[k] = short_first ? 0u : len[k];
+        real_len[k] = len[k];
     bool any_long = false;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -165,18 +168,12 @@ __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord 
             s[k] = (uint32_t)i < len[k] ? next[k] : s[k];
     }
     if (__ballot(any_long) != 0) {
-        // tokens of more than three bytes: their records (if not read yet), then bytes 3 .. 7 from
-        // the record and the rest from the class string
+        // tokens of more than three bytes: bytes 3 .. 7 from the record and the rest from the class
+        // string
         uint32_t longest = 0;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             if (len[k] > 3u) {
-                if (short_first) {
-                    const TokenRecord rec = tok_b[t[k]];
-                    pk[k] = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
-                    off[k] = rec.offset;
-                    real_len[k] = rec.length;
-                }
                 len[k] = real_len[k];
                 longest = max(longest, len[k]);
             } else {
@@ -223,6 +220,105 @@ __device__ __forceinline__ void walk_ranks(const EmitArgs &a, const TokenRecord 
             a.token_ids[pos] = token0 + (int32_t)t[k];
             a.next_states[pos] = (int32_t)s[k];
         }
+    }
+}
+
+// The same for large automata without structure, where the texture addresser is what bounds the
+// walk and most admissible tokens are short.  A token is read in its four-byte form (the classes
+// of its first three bytes and its length): consecutive ranks are tokens a few ids apart, and their
+// short forms share cache lines where their 16-byte records do not.  Byte 0 comes from row q in
+// LDS, byte 1 from the table; the few walks that are longer are put aside -- (rank, state so far)
+// in LDS -- and finished together by walk_deferred, so that their look-ups are issued by full
+// waves instead of by every wave that holds one of them.
+struct Deferred {
+    uint16_t *rank;            // [kDeferCap] rank within the part
+    uint32_t *state;           // [kDeferCap] state after two bytes
+};
+
+template <typename E>
+__device__ __forceinline__ void walk_deferred(const EmitArgs &a, const TokenRecord *__restrict__ tok_b,
+                                              const uint8_t *__restrict__ cls, const E *__restrict__ tab,
+                                              const uint16_t *list, const Deferred &d, const uint32_t n_def,
+                                              const int lane, const SpanOut &out, const uint32_t r0,
+                                              const uint32_t n_classes)
+{
+    for (uint32_t e0 = 0; e0 < n_def; e0 += kWave) {
+        const bool valid = e0 + (uint32_t)lane < n_def;
+        const uint32_t rel = valid ? (uint32_t)d.rank[e0 + lane] : 0u;
+        uint32_t s = valid ? d.state[e0 + lane] : 0u;
+        const TokenRecord rec = tok_b[list[rel]];
+        const uint64_t pk = ((uint64_t)rec.cls_hi << 32) | rec.cls_lo;
+        const uint32_t len = valid ? rec.length : 0u;
+#pragma unroll
+        for (int i = 2; i < kPackedClasses; ++i) {
+            if (__ballot((uint32_t)i < len) == 0)
+                break;
+            const uint32_t half = i < 4 ? (uint32_t)pk : (uint32_t)(pk >> 32);
+            const uint32_t c = (half >> (8 * (i & 3))) & 255u;
+            const uint32_t next = (uint32_t)tab[(uint32_t)i < len ? s * n_classes + c : 0u];
+            s = (uint32_t)i < len ? next : s;
+        }
+        for (uint32_t i = (uint32_t)kPackedClasses; __ballot(i < len) != 0; ++i) {
+            const uint32_t c = i < len ? (uint32_t)cls[rec.offset + i] : 0u;
+            const uint32_t next = (uint32_t)tab[i < len ? s * n_classes + c : 0u];
+            s = i < len ? next : s;
+        }
+        if (valid)
+            a.next_states[span_pos(out, r0 + rel)] = (int32_t)s;
+    }
+}
+
+template <typename E, int K>
+__device__ __forceinline__ void walk_ranks_short(const EmitArgs &a, const uint32_t *__restrict__ key_b,
+                                                 const E *__restrict__ tab, const uint16_t *list,
+                                                 const uint32_t *row_q, const int32_t q, const int32_t token0,
+                                                 const int lane, const SpanOut &out, const uint32_t r0,
+                                                 const uint32_t g0, const uint32_t r1, const uint32_t n_classes,
+                                                 const Deferred &d, uint32_t &n_def)
+{
+    uint32_t t[K], s[K], len[K], kk[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
+        t[k] = r < r1 ? (uint32_t)list[r - r0] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        kk[k] = key_b[t[k]];
+    bool some = false;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
+        len[k] = r < r1 ? kk[k] >> 24 : 0u;                 // (255: 255 bytes or more, the record knows)
+        s[k] = len[k] != 0u ? row_q[kk[k] & 255u] : (uint32_t)q;
+        some = some || len[k] > 1u;
+    }
+    if (__ballot(some) != 0) {
+        uint32_t next[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            next[k] = (uint32_t)tab[len[k] > 1u ? s[k] * n_classes + ((kk[k] >> 8) & 255u) : 0u];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            s[k] = len[k] > 1u ? next[k] : s[k];
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t r = g0 + (uint32_t)(k * kWave + lane);
+        const bool later = len[k] > 2u;
+        if (r < r1) {
+            const int64_t pos = span_pos(out, r);
+            a.token_ids[pos] = token0 + (int32_t)t[k];
+            if (!later)
+                a.next_states[pos] = (int32_t)s[k];
+        }
+        const uint64_t m = __ballot(later);
+        if (later) {
+            const uint32_t at = n_def + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            d.rank[at] = (uint16_t)(r - r0);
+            d.state[at] = s[k];
+        }
+        n_def += (uint32_t)__popcll(m);
     }
 }
 
@@ -508,7 +604,8 @@ __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__r
                                           const uint8_t *__restrict__ cls, const E *__restrict__ tab,
                                           const uint32_t *__restrict__ key,
                                           const int32_t q, const int32_t b0, const uint32_t part,
-                                          const uint32_t parts, const int lane, uint16_t *list, uint32_t *row_q)
+                                          const uint32_t parts, const int lane, uint16_t *list, uint32_t *row_q,
+                                          const Deferred later)
 {
     uint64_t A[kWalkBlocks];
     uint32_t own[kWalkBlocks], first[kWalkBlocks], n_w[kWalkBlocks];
@@ -610,15 +707,38 @@ __device__ __forceinline__ void emit_span(const EmitArgs &a, const uint64_t *__r
         }
         __builtin_amdgcn_wave_barrier();
         // ---- walk, up to kEmitK ranks per lane at a time
-        for (uint32_t g0 = r0; g0 < r1;) {
-            const uint32_t left = r1 - g0;
-            if (left > (uint32_t)kWave) {
-                walk_ranks<E, kEmitK>(a, tok_b, key_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes,
-                                      short_first);
-                g0 += (uint32_t)(kWave * kEmitK);
-            } else {
-                walk_ranks<E, 1>(a, tok_b, key_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes, short_first);
-                g0 += (uint32_t)kWave;
+        if (short_first) {
+            uint32_t n_def = 0;
+            for (uint32_t g0 = r0; g0 < r1;) {
+                if (n_def + (uint32_t)(kWave * kEmitK) > (uint32_t)kDeferCap) {
+                    __builtin_amdgcn_wave_barrier();
+                    walk_deferred<E>(a, tok_b, cls, tab, list, later, n_def, lane, out, r0, n_classes);
+                    n_def = 0;
+                    __builtin_amdgcn_wave_barrier();
+                }
+                const uint32_t left = r1 - g0;
+                if (left > (uint32_t)kWave) {
+                    walk_ranks_short<E, kEmitK>(a, key_b, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes,
+                                                later, n_def);
+                    g0 += (uint32_t)(kWave * kEmitK);
+                } else {
+                    walk_ranks_short<E, 1>(a, key_b, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes, later,
+                                           n_def);
+                    g0 += (uint32_t)kWave;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            walk_deferred<E>(a, tok_b, cls, tab, list, later, n_def, lane, out, r0, n_classes);
+        } else {
+            for (uint32_t g0 = r0; g0 < r1;) {
+                const uint32_t left = r1 - g0;
+                if (left > (uint32_t)kWave) {
+                    walk_ranks<E, kEmitK>(a, tok_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes);
+                    g0 += (uint32_t)(kWave * kEmitK);
+                } else {
+                    walk_ranks<E, 1>(a, tok_b, cls, tab, list, row_q, q, token0, lane, out, r0, g0, r1, n_classes);
+                    g0 += (uint32_t)kWave;
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -663,7 +783,7 @@ __global__ __launch_bounds__(kWave) void emit_csr(const EmitArgs a, const uint64
         // are the long ones, and what starts last is what the kernel ends with)
         const uint32_t q = a.st->use_sets != 0 ? a.order[slot] : slot;
         emit_span<E>(a, allow, tok, cls, tab, key, (int32_t)q, (int32_t)(span * kWalkBlocks), part, a.parts, lane,
-                     shared.walk.list, shared.walk.row);
+                     shared.walk.list, shared.walk.row, Deferred{shared.walk.later_rank, shared.walk.later_state});
     }
 }
 
