@@ -190,10 +190,15 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void walk_pairs(const WalkAr
                 for (uint32_t c = (uint32_t)lane; c < n_classes; c += kWave)
                     my.row[c] = tab[(uint32_t)q * n_classes + c];
                 __builtin_amdgcn_wave_barrier();
+                // (all look-ups of the state first: one wait for sixteen reads instead of sixteen waits)
+                E after[kChunksPerWave];
+#pragma unroll
+                for (int k = 0; k < kChunksPerWave; ++k)
+                    after[k] = my.row[first[k] & 255u];
 #pragma unroll
                 for (int k = 0; k < kChunksPerWave; ++k) {
                     const uint32_t len = first[k] >> 8;
-                    const E s1 = my.row[first[k] & 255u];
+                    const E s1 = after[k];
                     const bool alive = len != 0 && s1 != dead_e && !is_dead;
                     const uint64_t done = __ballot(alive && len == 1u);
                     const uint64_t more = __ballot(alive && len > 1u);
