@@ -212,7 +212,8 @@ struct FinishArgs {
     uint32_t expect;              // the counting kernels the host launches: 0 both, 1 token-set only, 2 dense only
 };
 
-// The part of the preparation that needs every state's pairs (one workgroup of kFinishThreads).
+// The part of the preparation that needs every state's pairs (two workgroups of kFinishThreads,
+// one for each of the first two jobs below; the third belongs to the second).
 //  - the order in which the counting walk takes the states: those with two or more pairs first
 //    (ascending), the others after them (descending, filled from the end).  Searches from branching
 //    states are the long ones, and a long one that starts last is what the whole kernel waits for;
@@ -250,26 +251,71 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
     __shared__ unsigned long long keys[kSetHashSlots];
     __shared__ uint64_t by_id[kSetCap];
     __shared__ uint32_t wave_sum[kWaves], wave_many[kWaves];
-    __shared__ uint32_t carry_s, carry_many_s, failed;
+    __shared__ uint32_t carry_s, carry_many_s, failed, pairs_s;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
+    const int32_t n = f.n_states;
+    // Two workgroups, two jobs that need nothing from each other: the order of the states
+    // (workgroup 0), and the class sets with the decision (workgroup 1).
+    if (blockIdx.x == 0) {
+        if (threadIdx.x == 0)
+            carry_many_s = 0;
+        __syncthreads();
+        for (int32_t c0 = 0; c0 < n; c0 += kFinishThreads * kFinishStates) {
+            uint32_t k[kFinishStates];
+#pragma unroll
+            for (int u = 0; u < kFinishStates; ++u) {
+                const int32_t i = c0 + u * kFinishThreads + (int32_t)threadIdx.x;
+                k[u] = i < n ? f.npairs[i] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kFinishStates; ++u) {
+                const int32_t i0 = c0 + u * kFinishThreads;
+                if (i0 >= n)
+                    break;                                       // uniform
+                const int32_t i = i0 + (int32_t)threadIdx.x;
+                const uint32_t x = k[u];
+                const uint64_t many = __ballot(i < n && x >= 2u);
+                if (lane == 0)
+                    wave_many[wave] = (uint32_t)__popcll(many);
+                __syncthreads();
+                uint32_t many_before = carry_many_s, all = 0;
+                for (int w = 0; w < kWaves; ++w) {
+                    if (w < wave)
+                        many_before += wave_many[w];
+                    all += wave_many[w];
+                }
+                if (i < n) {
+                    const uint32_t rank = many_before + __builtin_amdgcn_mbcnt_hi((uint32_t)(many >> 32),
+                                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)many, 0u));
+                    f.order[x >= 2u ? rank : (uint32_t)n - 1u - ((uint32_t)i - rank)] = (uint32_t)i;
+                }
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    carry_many_s += all;
+                __syncthreads();
+            }
+        }
+        return;
+    }
     if (threadIdx.x == 0) {
         carry_s = 0;
-        carry_many_s = 0;
         failed = 0;
+        pairs_s = 0;
     }
     if (threadIdx.x < kSetHashSlots)
         keys[threadIdx.x] = 0ull;
     const uint32_t long_tokens = st->long_tokens;
     __syncthreads();
-    const int32_t n = f.n_states;
     for (int32_t c0 = 0; c0 < n; c0 += kFinishThreads * kFinishStates) {
         uint32_t k[kFinishStates];
         unsigned long long m0[kFinishStates], m1[kFinishStates];
+        uint32_t mine = 0;
 #pragma unroll
         for (int u = 0; u < kFinishStates; ++u) {
             const int32_t i = c0 + u * kFinishThreads + (int32_t)threadIdx.x;
             k[u] = i < n ? f.npairs[i] : 0u;
+            mine += k[u];
         }
 #pragma unroll
         for (int u = 0; u < kFinishStates; ++u) {
@@ -277,44 +323,16 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
             m0[u] = k[u] > 0u ? f.pmask[i] : 0ull;
             m1[u] = k[u] > 1u ? f.pmask[(int64_t)n + i] : 0ull;
         }
-        // ---- the order of the states and the number of pairs
+        // ---- the number of pairs so far
 #pragma unroll
-        for (int u = 0; u < kFinishStates; ++u) {
-            const int32_t i0 = c0 + u * kFinishThreads;
-            if (i0 >= n)
-                break;                                           // uniform
-            const int32_t i = i0 + (int32_t)threadIdx.x;
-            const uint32_t x = k[u];
-            uint32_t incl = x;
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) {
-                const uint32_t up = __shfl_up(incl, d, kWave);
-                if (lane >= d)
-                    incl += up;
-            }
-            const uint64_t many = __ballot(i < n && x >= 2u);
-            if (lane == kWave - 1) {
-                wave_sum[wave] = incl;
-                wave_many[wave] = (uint32_t)__popcll(many);
-            }
-            __syncthreads();
-            uint32_t before = carry_s, many_before = carry_many_s;
-            for (int w = 0; w < wave; ++w) {
-                before += wave_sum[w];
-                many_before += wave_many[w];
-            }
-            if (i < n) {
-                const uint32_t rank = many_before + __builtin_amdgcn_mbcnt_hi((uint32_t)(many >> 32),
-                                                                              __builtin_amdgcn_mbcnt_lo((uint32_t)many, 0u));
-                f.order[x >= 2u ? rank : (uint32_t)n - 1u - ((uint32_t)i - rank)] = (uint32_t)i;
-            }
-            __syncthreads();
-            if (threadIdx.x == kFinishThreads - 1) {
-                carry_s = before + incl;
-                carry_many_s = many_before + (uint32_t)__popcll(many);
-            }
-            __syncthreads();
-        }
+        for (int o = 32; o >= 1; o >>= 1)
+            mine += __shfl_xor(mine, o, kWave);
+        if (lane == 0)
+            atomicAdd(&pairs_s, mine);
+        __syncthreads();
+        if (threadIdx.x == 0)
+            carry_s = pairs_s;
+        __syncthreads();
         // ---- the class sets into the table (an automaton with more than three pairs per state on
         //      average is not for the token-set walk: its sets may be too many to be worth entering;
         //      the decision below looks at the final count)
@@ -465,7 +483,7 @@ hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_voc
                            dfa.dead_state, p.live_words, reinterpret_cast<uint32_t *>(ws + p.off_tab), live,
                            static_cast<uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), static_cast<uint64_t *>(nullptr), st);
     if (with_sets)
-        hipLaunchKernelGGL(finish_sets, dim3(1), dim3(kFinishThreads), 0, stream, f, st);
+        hipLaunchKernelGGL(finish_sets, dim3(2), dim3(kFinishThreads), 0, stream, f, st);
     return hipGetLastError();
 }
 
