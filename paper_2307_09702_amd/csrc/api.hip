@@ -73,8 +73,15 @@ int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_b
     p->n_ranges = (n_states + p->states_per_wave - 1) / p->states_per_wave;
     if ((int64_t)p->n_groups * p->n_ranges > 0x7FFFFFFFll)
         return fail(FSMIDX_INVALID_ARG, "problem too large for one launch");
+    {
+        const int64_t want = (n_bytes / 16 + 255) / 256;
+        p->cls_groups = (int32_t)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+        p->pack_groups = (p->n_chunks * kChunkTokens + 255) / 256;
+        p->narrow_groups = (n_states + 3) / 4;
+    }
     size_t o = 0;
     p->off_status = o; o = align256(o + sizeof(Status));
+    p->off_badw = o;   o = align256(o + ((size_t)p->cls_groups + p->pack_groups + p->narrow_groups) * 4);
     p->off_sync = o;   o = align256(o + sizeof(SyncWords));
     p->off_cls = o;    o = align256(o + (size_t)n_bytes + 16);
     p->off_tok = o;    o = align256(o + (size_t)p->n_chunks * kChunkTokens * sizeof(TokenRecord));

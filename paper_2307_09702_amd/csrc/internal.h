@@ -50,6 +50,8 @@ enum : uint32_t {
     kBadClass = 2u,        // byte_to_class value >= n_classes
     kBadOffsets = 4u,      // offsets decreasing / outside [0, n_bytes] / not starting at 0
     kDeadNotAbsorbing = 8u,
+    kInputFlags = 15u,
+    kLongTokens = 16u,     // (not an error) some token is longer than kMaxSetDepth bytes; travels with the check bits
 };
 
 // One vocabulary token as the walk kernels read it: 16 bytes, loaded as one dwordx4.
@@ -81,7 +83,11 @@ struct Plan {
     int32_t states_per_wave = 0;   // dense path: consecutive states one wave walks
     int32_t n_ranges = 0;          // ceil(n_states / states_per_wave)
     bool sets_possible = false;    // host-side necessary conditions for the token-set path
+    // the preparation kernel's workgroups: first those that classify bytes, then those that pack
+    // tokens, then those that narrow states; each leaves one word of check bits
+    int32_t cls_groups = 0, pack_groups = 0, narrow_groups = 0;
     size_t off_status = 0;         // Status
+    size_t off_badw = 0;           // uint32 [cls_groups + pack_groups + narrow_groups] check bits per workgroup
     size_t off_sync = 0;           // SyncWords
     size_t off_cls = 0;            // uint8  [n_bytes]            class of every vocabulary byte
     size_t off_tok = 0;            // TokenRecord [n_chunks * 64]
@@ -123,6 +129,23 @@ struct Status {       // mirrored at off_status
     uint32_t n_long;       // length of the list of long (state, block) segments (token-set path)
     uint32_t feasible;     // the token-set kernels could have counted, but the host had launched only the dense one
 };
+
+// Transpose of the 64 x 64 bit matrix whose row i is the word x of lane i: afterwards bit i of
+// lane k's word is what bit k of lane i's word was.  Six rounds; round j swaps, between lanes
+// that differ in bit j of their number, the blocks of bits whose position differs in bit j.
+__device__ __forceinline__ uint64_t transpose_bits(uint64_t x, int lane)
+{
+    constexpr uint64_t kLow[6] = {0x5555555555555555ull, 0x3333333333333333ull, 0x0F0F0F0F0F0F0F0Full,
+                                  0x00FF00FF00FF00FFull, 0x0000FFFF0000FFFFull, 0x00000000FFFFFFFFull};
+#pragma unroll
+    for (int r = 5; r >= 0; --r) {
+        const int j = 1 << r;
+        const uint64_t low = kLow[r];                            // positions b with (b & j) == 0
+        const uint64_t other = __shfl_xor(x, j, kWave);
+        x = (lane & j) == 0 ? (x & low) | ((other << j) & ~low) : (x & ~low) | ((other >> j) & low);
+    }
+    return x;
+}
 
 int make_plan(int32_t n_states, int32_t n_classes, int32_t n_tokens, int64_t n_bytes, Plan *plan);
 

@@ -1,17 +1,18 @@
 // Input preparation for the index build: the alphabet of V is mapped to byte classes and the
 // transition function delta (Section 3, Definition 1) is narrowed, summarised and, for the
-// token-set walk, regrouped by target.  Three launches:
+// token-set walk, regrouped by target.  Two launches here (a third, token_sets, has a file of its own):
 //
-//  classify_bytes : class string of the whole vocabulary, one byte per vocabulary byte; also resets
-//                   the status words of the build and the words its later launches meet through
-//  pack_and_narrow, one launch for two jobs:
-//    pack_token   : one 16-byte record per token (leading classes, start, length)
-//    narrow_state : int32 table -> uint16/uint32 table + per-state mask of the classes a state
-//                   can read (the SIMD form of Algorithm 3's restriction to the states that can
-//                   read the first symbol); for automata with at most 64 classes also the state's
-//                   (target, class set) pairs, smallest class set first
-//  finish_sets    : one workgroup numbers the distinct class sets, orders the states for the
-//                   counting walk and decides whether the token-set kernels run
+//  prepare_all, one launch for three jobs that need nothing from each other:
+//    classify_bytes : class string of the whole vocabulary, one byte per vocabulary byte
+//    pack_token     : one 16-byte record per token (leading classes, start, length) and its
+//                     four-byte short form
+//    narrow_state   : int32 table -> uint16/uint32 table + per-state mask of the classes a state
+//                     can read (the SIMD form of Algorithm 3's restriction to the states that can
+//                     read the first symbol); for automata with at most 64 classes also the state's
+//                     (target, class set) pairs, smallest class set first
+//  finish_sets      : one workgroup gathers the check bits, numbers the distinct class sets, decides
+//                     whether the token-set kernels run and writes the status words of the build;
+//                     a second one orders the states for the counting walk
 //
 // Every value that later serves as an address (class id, transition target, offset) is range
 // checked here; bad values raise a flag bit and are replaced by harmless ones.
@@ -19,46 +20,32 @@
 
 namespace fsmidx {
 
-__global__ __launch_bounds__(256) void classify_bytes(const uint8_t *__restrict__ bytes, int64_t n_bytes,
-                                                      const uint8_t *__restrict__ byte_to_class,
-                                                      int32_t n_classes, uint8_t *__restrict__ cls,
-                                                      Status *st)
+// The byte-to-class map in LDS, every value range checked (a bad one counts as class 0).
+// Returns kBadClass if this thread's entry was bad.  256 threads.
+__device__ __forceinline__ uint32_t load_class_map(const uint8_t *__restrict__ byte_to_class, int32_t n_classes,
+                                                   uint8_t *map)
 {
-    __shared__ uint8_t map[256];
-    // The first kernel of a build: its first workgroup resets the status words before it (and only
-    // it, in this kernel) reports into them; every later kernel finds them reset.
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        {
-            st->nnz = 0;
-            st->flags = 0;
-            st->use_sets = 0;
-            st->n_sets = 0;
-            st->n_pairs = 0;
-            st->long_tokens = 0;
-            st->overflow = 0;
-            st->n_long = 0;
-            st->feasible = 0;
-        }
-    }
     uint32_t bad = 0;
-    {
-        uint32_t c = byte_to_class[threadIdx.x];
-        if (c >= (uint32_t)n_classes) {
-            bad = 1;
-            c = 0;
-        }
-        map[threadIdx.x] = (uint8_t)c;
+    uint32_t c = byte_to_class[threadIdx.x];
+    if (c >= (uint32_t)n_classes) {
+        bad = kBadClass;
+        c = 0;
     }
-    __syncthreads();
-    if (bad && blockIdx.x == 0)
-        atomicOr(&st->flags, kBadClass);
+    map[threadIdx.x] = (uint8_t)c;
+    return bad;
+}
+
+// Workgroup `group` of `n_groups`: its share of the class string.
+__device__ __forceinline__ void classify_bytes(const uint8_t *__restrict__ bytes, int64_t n_bytes, const uint8_t *map,
+                                               uint8_t *__restrict__ cls, int32_t group, int32_t n_groups)
+{
     // 16 bytes per thread per step, tail byte-wise
     const int64_t n_vec = n_bytes / 16;
     const uint4 *src = reinterpret_cast<const uint4 *>(bytes);
     uint4 *dst = reinterpret_cast<uint4 *>(cls);
     const bool aligned = ((reinterpret_cast<uintptr_t>(bytes) | reinterpret_cast<uintptr_t>(cls)) & 15) == 0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)n_groups * blockDim.x;
+    const int64_t tid = (int64_t)group * blockDim.x + threadIdx.x;
     if (aligned) {
         for (int64_t i = tid; i < n_vec; i += stride) {
             uint4 v = src[i];
@@ -80,13 +67,14 @@ __global__ __launch_bounds__(256) void classify_bytes(const uint8_t *__restrict_
 }
 
 // The record of token slot t (slots past the last token get an empty record).
-__device__ __forceinline__ void pack_token(int32_t t, const int64_t *__restrict__ offsets, int32_t n_tokens,
-                                           int64_t n_bytes, int32_t eos, int32_t n_slots,
-                                           const uint8_t *__restrict__ cls, TokenRecord *__restrict__ tok,
-                                           uint32_t *__restrict__ key, Status *st)
+__device__ __forceinline__ uint32_t pack_token(int32_t t, const int64_t *__restrict__ offsets, int32_t n_tokens,
+                                               int64_t n_bytes, int32_t eos, int32_t n_slots,
+                                               const uint8_t *__restrict__ bytes, const uint8_t *map,
+                                               TokenRecord *__restrict__ tok, uint32_t *__restrict__ key)
 {
     if (t >= n_slots)
-        return;
+        return 0;
+    uint32_t bad = 0;
     TokenRecord r = {0, 0, 0, 0};
     if (t < n_tokens) {
         const int64_t a = offsets[t], b = offsets[t + 1];
@@ -94,17 +82,19 @@ __device__ __forceinline__ void pack_token(int32_t t, const int64_t *__restrict_
         if (t == 0 && a != 0) ok = false;
         if (t == n_tokens - 1 && b != n_bytes) ok = false;
         if (!ok) {
-            atomicOr(&st->flags, kBadOffsets);
+            bad = kBadOffsets;
         } else if (t != eos) {
             const uint32_t len = (uint32_t)(b - a);
             r.offset = (uint32_t)a;
             r.length = len;
-            // eight independent loads (the class string is padded), then the bytes past the end are
-            // masked away: a loop to the token's own length would be eight dependent round trips
+            // eight independent loads (classified here, straight from the vocabulary's bytes: the
+            // class string is being written by other workgroups of the same launch), then the bytes
+            // past the end are masked away: a loop to the token's own length would be eight
+            // dependent round trips
             uint64_t pk = 0;
 #pragma unroll
             for (int i = 0; i < kPackedClasses; ++i)
-                pk |= (uint64_t)cls[a + i] << (8 * i);
+                pk |= (uint64_t)(a + i < n_bytes ? map[bytes[a + i]] : 0) << (8 * i);
             if (len < (uint32_t)kPackedClasses)
                 pk &= (1ull << (8 * len)) - 1ull;
             r.cls_lo = (uint32_t)pk;
@@ -115,10 +105,10 @@ __device__ __forceinline__ void pack_token(int32_t t, const int64_t *__restrict_
     // the short form for the passes that mostly meet short tokens: three classes and the length in
     // one word (a length of 255 says: look at the record)
     key[t] = (r.cls_lo & 0xFFFFFFu) | (r.length < 255u ? r.length : 255u) << 24;
-    // the token-set path handles tokens of up to kMaxSetDepth bytes (a plain store: every writer
-    // writes the same value)
+    // the token-set path handles tokens of up to kMaxSetDepth bytes
     if (r.length > (uint32_t)kMaxSetDepth)
-        st->long_tokens = 1;
+        bad |= kLongTokens;
+    return bad;
 }
 
 __device__ __forceinline__ uint32_t hash_mask(uint64_t m)
@@ -137,11 +127,11 @@ __device__ __forceinline__ uint32_t hash_mask(uint64_t m)
 // lowest class), so that the widest set -- typically the one that keeps a token set walking -- is
 // last and can be followed without a stack frame.
 template <typename E>
-__device__ __forceinline__ void narrow_state(const int32_t q, const int lane, const int32_t *__restrict__ trans,
-                                             int32_t n_states, int32_t n_classes, int32_t dead, int32_t live_words,
-                                             E *__restrict__ tab, uint64_t *__restrict__ live,
-                                             uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
-                                             uint64_t *__restrict__ pmask, Status *st)
+__device__ __forceinline__ uint32_t narrow_state(const int32_t q, const int lane, const int32_t *__restrict__ trans,
+                                                 int32_t n_states, int32_t n_classes, int32_t dead, int32_t live_words,
+                                                 E *__restrict__ tab, uint64_t *__restrict__ live,
+                                                 uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
+                                                 uint64_t *__restrict__ pmask)
 {
     const E dead_e = dead >= 0 ? (E)dead : (E)~(E)0;
     uint32_t flags = 0;
@@ -197,8 +187,7 @@ __device__ __forceinline__ void narrow_state(const int32_t q, const int lane, co
                 npairs[q] = k;
         }
     }
-    if (flags)
-        atomicOr(&st->flags, flags);
+    return flags;
 }
 
 struct FinishArgs {
@@ -208,8 +197,10 @@ struct FinishArgs {
     uint32_t *pslot;              // [n_classes][n_states]
     uint32_t *order;              // [n_states]
     uint64_t *class_sets;         // [64][kSetCap / 64]
-    int32_t n_states;
+    int32_t n_states, n_classes;
     uint32_t expect;              // the counting kernels the host launches: 0 both, 1 token-set only, 2 dense only
+    const uint32_t *badw;         // [n_badw] check bits of the preparation kernel's workgroups
+    int32_t n_badw;
 };
 
 // The part of the preparation that needs every state's pairs (two workgroups of kFinishThreads,
@@ -232,7 +223,12 @@ __device__ __forceinline__ uint32_t table_slot(unsigned long long *keys, unsigne
 {
     uint32_t h = hash_mask(key);
     for (int probe = 0; probe < kSetHashSlots; ++probe) {
-        const unsigned long long old = atomicCAS(&keys[h], 0ull, key);
+        // Looked at before it is claimed: an automaton has few distinct class sets, so nearly every
+        // call finds its set entered already, and lanes reading one address are served together
+        // while their atomics on it would take turns.
+        unsigned long long old = __hip_atomic_load(&keys[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (old == 0ull)
+            old = atomicCAS(&keys[h], 0ull, key);
         if (old == 0ull || old == key)
             return h;
         h = (h + 1) & (kSetHashSlots - 1);
@@ -255,9 +251,10 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int32_t n = f.n_states;
-    // Two workgroups, two jobs that need nothing from each other: the order of the states
-    // (workgroup 0), and the class sets with the decision (workgroup 1).
-    if (blockIdx.x == 0) {
+    // Two workgroups, two jobs that need nothing from each other: the class sets with the decision
+    // and the status words (workgroup 0; the only one when the token-set kernels are out of the
+    // question), and the order of the states (workgroup 1).
+    if (blockIdx.x == 1) {
         if (threadIdx.x == 0)
             carry_many_s = 0;
         __syncthreads();
@@ -298,16 +295,41 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
         }
         return;
     }
+    constexpr int kHeavyCap = 1024;
+    __shared__ uint32_t checks_s, heavy_n;
+    __shared__ uint32_t heavy_list[kHeavyCap];
     if (threadIdx.x == 0) {
+        heavy_n = 0;
         carry_s = 0;
         failed = 0;
         pairs_s = 0;
+        checks_s = 0;
     }
     if (threadIdx.x < kSetHashSlots)
         keys[threadIdx.x] = 0ull;
-    const uint32_t long_tokens = st->long_tokens;
     __syncthreads();
-    for (int32_t c0 = 0; c0 < n; c0 += kFinishThreads * kFinishStates) {
+    // What the preparation kernel's workgroups found wrong with the input (and whether some token
+    // is too long for the token-set walk).  The words are asked for here and looked at after the
+    // first states' loads have been issued: one trip to memory for both.
+    uint32_t my_checks = 0;
+    for (int32_t i0 = 0; i0 < f.n_badw; i0 += 4 * kFinishThreads) {
+        uint32_t w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                            // four loads in flight
+            const int32_t i = i0 + u * kFinishThreads + (int32_t)threadIdx.x;
+            w[u] = i < f.n_badw ? f.badw[i] : 0u;
+        }
+        my_checks |= (w[0] | w[1]) | (w[2] | w[3]);
+    }
+    const bool with_sets = f.npairs != nullptr;
+    if (!with_sets) {
+        if (my_checks)
+            atomicOr(&checks_s, my_checks);
+        __syncthreads();
+    }
+    for (int32_t c0 = 0; with_sets && c0 < n; c0 += kFinishThreads * kFinishStates) {
+        // pair counts and the class sets of the first two pairs, none of the loads waiting for
+        // another (a set that does not exist is whatever the array held: masked right below)
         uint32_t k[kFinishStates];
         unsigned long long m0[kFinishStates], m1[kFinishStates];
         uint32_t mine = 0;
@@ -315,14 +337,19 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
         for (int u = 0; u < kFinishStates; ++u) {
             const int32_t i = c0 + u * kFinishThreads + (int32_t)threadIdx.x;
             k[u] = i < n ? f.npairs[i] : 0u;
-            mine += k[u];
+            m0[u] = i < n ? f.pmask[i] : 0ull;
+            m1[u] = i < n && f.n_classes > 1 ? f.pmask[(int64_t)n + i] : 0ull;
         }
 #pragma unroll
         for (int u = 0; u < kFinishStates; ++u) {
-            const int32_t i = c0 + u * kFinishThreads + (int32_t)threadIdx.x;
-            m0[u] = k[u] > 0u ? f.pmask[i] : 0ull;
-            m1[u] = k[u] > 1u ? f.pmask[(int64_t)n + i] : 0ull;
+            mine += k[u];
+            if (k[u] < 1u)
+                m0[u] = 0ull;
+            if (k[u] < 2u)
+                m1[u] = 0ull;
         }
+        if (c0 == 0 && my_checks)
+            atomicOr(&checks_s, my_checks);
         // ---- the number of pairs so far
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1)
@@ -336,7 +363,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
         // ---- the class sets into the table (an automaton with more than three pairs per state on
         //      average is not for the token-set walk: its sets may be too many to be worth entering;
         //      the decision below looks at the final count)
-        if (carry_s > 3u * (uint32_t)n || long_tokens != 0)
+        if (carry_s > 3u * (uint32_t)n || (checks_s & kLongTokens) != 0)
             continue;                                            // uniform
 #pragma unroll
         for (int u = 0; u < kFinishStates; ++u) {
@@ -353,7 +380,16 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
                     failed = 1;
                 f.pslot[(int64_t)n + i] = h;
             }
-            uint64_t heavy = __ballot(k[u] > 2u);
+            // a state with more pairs goes on a list (or, if the list is full, is taken by its wave
+            // as a whole right away, lane j loading the state's pair j: one state after the other)
+            bool listed = false;
+            if (k[u] > 2u) {
+                const uint32_t at = atomicAdd(&heavy_n, 1u);
+                listed = at < (uint32_t)kHeavyCap;
+                if (listed)
+                    heavy_list[at] = (uint32_t)i | k[u] << 16;   // (at most 65535 states and 64 classes here)
+            }
+            uint64_t heavy = __ballot(k[u] > 2u && !listed);
             while (heavy != 0) {
                 const int src = __builtin_ctzll(heavy);
                 heavy &= heavy - 1;
@@ -368,10 +404,30 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
                 }
             }
         }
+        // the listed states, sixteen lanes to a state, so that the loads of 64 states are in flight
+        // together
+        __syncthreads();
+        const uint32_t n_listed = heavy_n < (uint32_t)kHeavyCap ? heavy_n : (uint32_t)kHeavyCap;
+        for (uint32_t h0 = threadIdx.x >> 4; h0 < n_listed; h0 += kFinishThreads / 16) {
+            const uint32_t e = heavy_list[h0];
+            const int32_t ii = (int32_t)(e & 0xFFFFu);
+            for (uint32_t j = 2u + (threadIdx.x & 15u); j < e >> 16; j += 16u) {
+                const int64_t at = (int64_t)j * n + ii;
+                const uint32_t h = table_slot(keys, f.pmask[at]);
+                if (h == (uint32_t)kSetHashSlots)
+                    failed = 1;
+                f.pslot[at] = h;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0)
+            heavy_n = 0;
     }
     __syncthreads();
     const uint32_t n_pairs = carry_s;
-    bool ok = n_pairs <= 3u * (uint32_t)n && long_tokens == 0;       // uniform over the workgroup
+    const uint32_t checks = checks_s;
+    const uint32_t long_tokens = (checks & kLongTokens) != 0 ? 1u : 0u;
+    bool ok = with_sets && n_pairs <= 3u * (uint32_t)n && long_tokens == 0;      // uniform over the workgroup
     uint32_t n_sets = 0;
     if (ok) {
         // number the occupied slots
@@ -396,48 +452,72 @@ __global__ __launch_bounds__(kFinishThreads) void finish_sets(const FinishArgs f
         }
         __syncthreads();
         ok = failed == 0 && n_sets <= (uint32_t)kSetCap;
-        // the transpose: for every class, the sets that contain it (bit k of word k / 64 = set k)
-        if (ok && threadIdx.x < 64) {
-            uint64_t w[kSetCap / 64] = {};
-            for (uint32_t k2 = 0; k2 < n_sets; ++k2)
-                if ((by_id[k2] >> threadIdx.x) & 1ull)
-                    w[k2 / 64] |= 1ull << (k2 & 63);
-            for (int j = 0; j < kSetCap / 64; ++j)
-                f.class_sets[threadIdx.x * (kSetCap / 64) + j] = w[j];
-        }
+        // the transpose: for every class, the sets that contain it (bit k of word k / 64 = set k).
+        // Wave w holds the class sets of sets 64 w .. 64 w + 63, one per lane, as a 64 x 64 bit
+        // matrix; transposed, lane c has word w of class c.
+        static_assert(kSetCap % kWave == 0 && kSetCap <= kFinishThreads, "whole waves hold the sets");
+        if (ok && threadIdx.x < kSetCap)
+            f.class_sets[lane * (kSetCap / 64) + wave] =
+                transpose_bits(threadIdx.x < n_sets ? by_id[threadIdx.x] : 0ull, lane);
     }
+    // every status word of the build is written here, once: nothing before this kernel touches them
     if (threadIdx.x == 0) {
+        st->nnz = 0;
+        st->flags = checks & kInputFlags;
+        st->long_tokens = long_tokens;
+        st->n_long = 0;
         st->n_sets = n_sets;
         st->n_pairs = n_pairs;
         st->use_sets = ok && f.expect != 2u ? 1u : 0u;
-        if (ok && f.expect == 2u)
-            st->feasible = 1;                                    // the dense kernel counts; the host learns for next time
-        if (!ok && f.expect == 1u)
-            st->overflow = 2;                                    // nobody else will count: the host has to ask again
+        st->feasible = ok && f.expect == 2u ? 1u : 0u;           // the dense kernel counts; the host learns for next time
+        st->overflow = !ok && f.expect == 1u ? 2u : 0u;          // nobody else will count: the host has to ask again
     }
 }
 
-// The first `pack_groups` workgroups pack 256 token slots each, the others narrow four states
-// each, one wave per state (neither job needs the other; both need classify_bytes to have run).
+// One launch for three jobs that need nothing from each other: the first cls_groups workgroups
+// write the class string, the next pack_groups pack 256 token slots each (classifying the bytes
+// they need themselves), the others narrow four states each, one wave per state.  Every workgroup
+// leaves its check bits in a word of its own: the status words are written by the kernel after
+// this one, so nothing here has to be ordered against their reset.
 template <typename E>
-__global__ __launch_bounds__(256) void pack_and_narrow(int32_t pack_groups, const int64_t *__restrict__ offsets,
-                                                       int32_t n_tokens, int64_t n_bytes, int32_t eos, int32_t n_slots,
-                                                       const uint8_t *__restrict__ cls, TokenRecord *__restrict__ tok,
-                                                       uint32_t *__restrict__ key,
-                                                       const int32_t *__restrict__ trans, int32_t n_states,
-                                                       int32_t n_classes, int32_t dead, int32_t live_words,
-                                                       E *__restrict__ tab, uint64_t *__restrict__ live,
-                                                       uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
-                                                       uint64_t *__restrict__ pmask, Status *st)
+__global__ __launch_bounds__(256) void prepare_all(int32_t cls_groups, int32_t pack_groups,
+                                                   const uint8_t *__restrict__ bytes, int64_t n_bytes,
+                                                   const uint8_t *__restrict__ byte_to_class, uint8_t *__restrict__ cls,
+                                                   const int64_t *__restrict__ offsets, int32_t n_tokens, int32_t eos,
+                                                   int32_t n_slots, TokenRecord *__restrict__ tok,
+                                                   uint32_t *__restrict__ key,
+                                                   const int32_t *__restrict__ trans, int32_t n_states,
+                                                   int32_t n_classes, int32_t dead, int32_t live_words,
+                                                   E *__restrict__ tab, uint64_t *__restrict__ live,
+                                                   uint32_t *__restrict__ npairs, uint32_t *__restrict__ pairs,
+                                                   uint64_t *__restrict__ pmask, uint32_t *__restrict__ badw)
 {
-    if ((int32_t)blockIdx.x < pack_groups) {
-        pack_token((int32_t)(blockIdx.x * blockDim.x + threadIdx.x), offsets, n_tokens, n_bytes, eos, n_slots, cls, tok, key, st);
-        return;
+    __shared__ uint8_t map[256];
+    __shared__ uint32_t bad_s;
+    if (threadIdx.x == 0)
+        bad_s = 0;
+    uint32_t bad = 0;
+    const int32_t group = (int32_t)blockIdx.x;
+    if (group < cls_groups + pack_groups) {
+        bad = load_class_map(byte_to_class, n_classes, map);
+        __syncthreads();
+        if (group < cls_groups)
+            classify_bytes(bytes, n_bytes, map, cls, group, cls_groups);
+        else
+            bad |= pack_token((group - cls_groups) * 256 + (int32_t)threadIdx.x, offsets, n_tokens, n_bytes, eos, n_slots,
+                              bytes, map, tok, key);
+    } else {
+        __syncthreads();
+        const int32_t q = (group - cls_groups - pack_groups) * 4 + (int32_t)(threadIdx.x >> 6);
+        if (q < n_states)
+            bad = narrow_state<E>(q, threadIdx.x & (kWave - 1), trans, n_states, n_classes, dead, live_words, tab, live,
+                                  npairs, pairs, pmask);
     }
-    const int32_t q = ((int32_t)blockIdx.x - pack_groups) * 4 + (int32_t)(threadIdx.x >> 6);
-    if (q < n_states)
-        narrow_state<E>(q, threadIdx.x & (kWave - 1), trans, n_states, n_classes, dead, live_words, tab, live, npairs,
-                        pairs, pmask, st);
+    if (bad)
+        atomicOr(&bad_s, bad);
+    __syncthreads();
+    if (threadIdx.x == 0)
+        badw[group] = bad_s;
 }
 
 hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_vocab &vocab, char *ws, int expect,
@@ -449,6 +529,7 @@ hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_voc
     TokenRecord *tok = reinterpret_cast<TokenRecord *>(ws + p.off_tok);
     uint32_t *key = reinterpret_cast<uint32_t *>(ws + p.off_key);
     uint64_t *live = reinterpret_cast<uint64_t *>(ws + p.off_live);
+    uint32_t *badw = reinterpret_cast<uint32_t *>(ws + p.off_badw);
     const bool with_sets = p.sets_possible;
     uint32_t *npairs = with_sets ? reinterpret_cast<uint32_t *>(ws + p.off_npairs) : nullptr;
     uint32_t *pairs = with_sets ? reinterpret_cast<uint32_t *>(ws + p.off_pairs) : nullptr;
@@ -461,29 +542,26 @@ hipError_t launch_prepare(const Plan &p, const fsmidx_dfa &dfa, const fsmidx_voc
     f.order = with_sets ? reinterpret_cast<uint32_t *>(ws + p.off_order) : nullptr;
     f.class_sets = with_sets ? reinterpret_cast<uint64_t *>(ws + p.off_clsets) : nullptr;
     f.n_states = p.n_states;
+    f.n_classes = p.n_classes;
     f.expect = (uint32_t)expect;
+    f.badw = badw;
+    f.n_badw = p.cls_groups + p.pack_groups + p.narrow_groups;
 
-    {
-        int64_t want = (p.n_bytes / 16 + 255) / 256;
-        int blocks = (int)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
-        hipLaunchKernelGGL(classify_bytes, dim3(blocks), dim3(256), 0, stream, vocab.bytes, p.n_bytes,
-                           dfa.byte_to_class, p.n_classes, cls, st);
-    }
     const int32_t n_slots = p.n_chunks * kChunkTokens;
-    const int32_t pack_groups = (n_slots + 255) / 256;
-    const dim3 grid((unsigned)(pack_groups + (p.n_states + 3) / 4));
+    const dim3 grid((unsigned)f.n_badw);
     if (p.entry_bytes == 2)
-        hipLaunchKernelGGL(pack_and_narrow<uint16_t>, grid, dim3(256), 0, stream, pack_groups, vocab.offsets, p.n_tokens,
-                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, key, dfa.trans, p.n_states, p.n_classes,
-                           dfa.dead_state, p.live_words, reinterpret_cast<uint16_t *>(ws + p.off_tab), live, npairs, pairs,
-                           pmask, st);
+        hipLaunchKernelGGL(prepare_all<uint16_t>, grid, dim3(256), 0, stream, p.cls_groups, p.pack_groups, vocab.bytes,
+                           p.n_bytes, dfa.byte_to_class, cls, vocab.offsets, p.n_tokens, vocab.eos_token_id, n_slots, tok,
+                           key, dfa.trans, p.n_states, p.n_classes, dfa.dead_state, p.live_words,
+                           reinterpret_cast<uint16_t *>(ws + p.off_tab), live, npairs, pairs, pmask, badw);
     else
-        hipLaunchKernelGGL(pack_and_narrow<uint32_t>, grid, dim3(256), 0, stream, pack_groups, vocab.offsets, p.n_tokens,
-                           p.n_bytes, vocab.eos_token_id, n_slots, cls, tok, key, dfa.trans, p.n_states, p.n_classes,
-                           dfa.dead_state, p.live_words, reinterpret_cast<uint32_t *>(ws + p.off_tab), live,
-                           static_cast<uint32_t *>(nullptr), static_cast<uint32_t *>(nullptr), static_cast<uint64_t *>(nullptr), st);
-    if (with_sets)
-        hipLaunchKernelGGL(finish_sets, dim3(2), dim3(kFinishThreads), 0, stream, f, st);
+        hipLaunchKernelGGL(prepare_all<uint32_t>, grid, dim3(256), 0, stream, p.cls_groups, p.pack_groups, vocab.bytes,
+                           p.n_bytes, dfa.byte_to_class, cls, vocab.offsets, p.n_tokens, vocab.eos_token_id, n_slots, tok,
+                           key, dfa.trans, p.n_states, p.n_classes, dfa.dead_state, p.live_words,
+                           reinterpret_cast<uint32_t *>(ws + p.off_tab), live, static_cast<uint32_t *>(nullptr),
+                           static_cast<uint32_t *>(nullptr), static_cast<uint64_t *>(nullptr), badw);
+    // (without the token-set kernels: one workgroup, which gathers the check bits and writes the status)
+    hipLaunchKernelGGL(finish_sets, dim3(with_sets ? 2 : 1), dim3(kFinishThreads), 0, stream, f, st);
     return hipGetLastError();
 }
 

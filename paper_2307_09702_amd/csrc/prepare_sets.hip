@@ -41,23 +41,6 @@ __device__ __forceinline__ void state_record(const uint32_t *__restrict__ npairs
     srec[q] = r;
 }
 
-// Transpose of the 64 x 64 bit matrix whose row i is the word x of lane i: afterwards bit i of
-// lane k's word is what bit k of lane i's word was.  Six rounds; round j swaps, between lanes
-// that differ in bit j of their number, the blocks of bits whose position differs in bit j.
-__device__ __forceinline__ uint64_t transpose_bits(uint64_t x, int lane)
-{
-    constexpr uint64_t kLow[6] = {0x5555555555555555ull, 0x3333333333333333ull, 0x0F0F0F0F0F0F0F0Full,
-                                  0x00FF00FF00FF00FFull, 0x0000FFFF0000FFFFull, 0x00000000FFFFFFFFull};
-#pragma unroll
-    for (int r = 5; r >= 0; --r) {
-        const int j = 1 << r;
-        const uint64_t low = kLow[r];                            // positions b with (b & j) == 0
-        const uint64_t other = __shfl_xor(x, j, kWave);
-        x = (lane & j) == 0 ? (x & low) | ((other << j) & ~low) : (x & ~low) | ((other >> j) & low);
-    }
-    return x;
-}
-
 // One wave per (group of kSetChunks consecutive chunks of 64 tokens, byte position d): if some
 // token of the group has a byte at position d, the end-of-token words E[d] of the group's chunks
 // and one word U[d][set] per chunk and class set.  Lane k ends up with the words of set k for all
