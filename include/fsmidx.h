@@ -426,6 +426,56 @@ int fsmidx_restrict_fill(const fsmidx_csr *index, const uint8_t *keep_dev, const
                          int32_t *token_ids_out_dev, int32_t *next_states_out_dev, int64_t capacity, void *stream);
 
 /*
+ * The scanner step of parser-guided generation (Section 4 and Section 4.1).  Every parse state
+ * reads an ordered list of terminal symbols and scans with the union of their automata.  A front
+ * end (not part of this library) supplies all these scanners side by side in one automaton
+ * `scanner` (DEVICE pointers as for fsmidx_build_count; only n_states, n_classes, trans and
+ * dead_state are read), and for every state q
+ *     completes[q]         uint64: bit t set iff q is a final state of terminal t (t < 64; the
+ *                          terminals are numbered in the order of the parser's lists)
+ *     scanner_of_state[q]  the parse state whose scanner q belongs to (read only for states that
+ *                          complete a terminal)
+ * and the parser's shift moves as a table
+ *     shift[p * n_terminals + t]  the state in which scanning goes on after terminal t has been
+ *                          read in parse state p (the start state of the following parse state's
+ *                          scanner), or -1 if parse state p does not read t.
+ * The stack of the pushdown automaton, its pre-image and the trie index over stack values
+ * (Section 4.1, last paragraphs) are outside this step.
+ *
+ * fsmidx_scanner_terminal_sets writes possible_out[q] = the terminals that the characters read so
+ * far can still become: bit t is set iff some string, possibly empty, leads from q to a state that
+ * completes t (the set V of Section 4.1, which shrinks while characters arrive).  The stream is
+ * synchronised once per 4 to 64 launches; *launches_host (may be NULL) receives the number of
+ * launches up to and including the first that changed nothing.
+ *
+ * fsmidx_scanner_restart_table writes the transition function that lets a vocabulary string finish
+ * one terminal and begin the next (Section 4, the strings " " and "oo(" after "def f"):
+ *     trans_out[q][c] = trans[q][c]                       if that is not dead_state,
+ *                     = trans[shift[p(q)][t]][c]          otherwise, for the lowest t that q
+ *                                                         completes with shift[p(q)][t] >= 0 and
+ *                                                         trans[shift[p(q)][t]][c] != dead_state,
+ *                     = dead_state                        if there is no such t.
+ * An automaton with trans_out in place of trans (same byte_to_class, accept, dead_state) is indexed
+ * by the build calls like any other.  With dead_state = -1 the table is copied.  The stream is
+ * synchronised once.
+ *
+ *   `workspace`: device, 256-byte aligned, fsmidx_scanner_workspace_bytes(n_states, n_classes)
+ * bytes; both calls overwrite it.  All arrays are DEVICE memory of the caller: completes and
+ * possible_out [n_states] (different arrays), scanner_of_state [n_states], shift [n_parse_states x
+ * n_terminals], trans_out [n_states x n_classes] (not the scanner's own table).  Values that would
+ * serve as addresses are range checked on the device (FSMIDX_BAD_DEVICE_INPUT; the outputs are
+ * then unspecified but every access stayed in bounds).
+ */
+int fsmidx_scanner_workspace_bytes(int32_t n_states, int32_t n_classes, size_t *bytes);
+int fsmidx_scanner_terminal_sets(const fsmidx_dfa *scanner, const uint64_t *completes_dev, void *workspace,
+                                 size_t workspace_bytes, uint64_t *possible_out_dev /* [n_states] */,
+                                 int32_t *launches_host, void *stream);
+int fsmidx_scanner_restart_table(const fsmidx_dfa *scanner, const uint64_t *completes_dev,
+                                 const int32_t *scanner_of_state_dev, const int32_t *shift_dev, int32_t n_parse_states,
+                                 int32_t n_terminals, void *workspace, size_t workspace_bytes,
+                                 int32_t *trans_out_dev /* [n_states x n_classes] */, void *stream);
+
+/*
  * Kernel timing for benchmarks.  After fsmidx_profile_enable(1) the calling thread's build,
  * mask_logits, advance_states, masked_argmax and masked_sample calls bracket each phase's kernels
  * with HIP events on the stream they are given (enable(0) stops that; either call resets the

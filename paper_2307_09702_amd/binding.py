@@ -29,6 +29,7 @@ EXPORTS = ("fsmidx_last_error", "fsmidx_validate_host", "fsmidx_build_index", "f
            "fsmidx_dedupe_workspace_bytes", "fsmidx_dedupe_rows", "fsmidx_dedupe_fill",
            "fsmidx_minimise_workspace_bytes", "fsmidx_minimise_dfa",
            "fsmidx_reach_workspace_bytes", "fsmidx_reachable_states", "fsmidx_restrict_rows", "fsmidx_restrict_fill",
+           "fsmidx_scanner_workspace_bytes", "fsmidx_scanner_terminal_sets", "fsmidx_scanner_restart_table",
            "fsmidx_profile_enable", "fsmidx_profile_read")
 
 
@@ -121,10 +122,18 @@ def load():
                                             POINTER(c_int32), c_void_p]
     lib.fsmidx_restrict_rows.argtypes = [POINTER(CCsr), c_void_p, c_void_p, c_size_t, c_void_p, POINTER(c_int64), c_void_p]
     lib.fsmidx_restrict_fill.argtypes = [POINTER(CCsr), c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
+    lib.fsmidx_scanner_workspace_bytes.argtypes = [c_int32, c_int32, POINTER(c_size_t)]
+    lib.fsmidx_scanner_terminal_sets.argtypes = [POINTER(CDfa), c_void_p, c_void_p, c_size_t, c_void_p, POINTER(c_int32),
+                                                 c_void_p]
+    lib.fsmidx_scanner_restart_table.argtypes = [POINTER(CDfa), c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p,
+                                                 c_size_t, c_void_p, c_void_p]
     lib.fsmidx_profile_enable.argtypes = [ctypes.c_int]
     lib.fsmidx_profile_read.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64)]
     for name in EXPORTS:
         fn = getattr(lib, name)
+        if fn.argtypes is None:
+            # (without them ctypes passes a Python int as a 32-bit int: a device address would be cut in half)
+            raise RuntimeError(f"binding.load: {name} has no argument types")
         if name not in ("fsmidx_last_error", "fsmidx_free_index"):
             fn.restype = ctypes.c_int
     _lib = lib
@@ -302,6 +311,55 @@ class DeviceMinimised:
         del ws
         self.n_states, self.n_classes, self.dead_state = int(out.n_states), int(out.n_classes), int(out.dead_state)
         self.trans = self.trans_full[:self.n_states * self.n_classes].view(self.n_states, self.n_classes)
+
+
+class DeviceScanner:
+    """The scanners of all parse states in one automaton, on the device (fsmidx_scanner_*).
+    ``trans`` int32 [Q, C], ``completes`` uint64 [Q], ``scanner_of_state`` int32 [Q], ``shift`` int32
+    [n_parse_states, n_terminals]: numpy arrays or device tensors (uint64 as int64 bit patterns)."""
+
+    def __init__(self, trans, dead_state, completes, scanner_of_state, shift, device="cuda:0"):
+        import torch
+        self.device = torch.device(device)
+
+        def to(a, dt):
+            if hasattr(a, "data_ptr") and not isinstance(a, np.ndarray):
+                return a
+            return torch.from_numpy(np.ascontiguousarray(np.asarray(a, dtype=dt))).to(self.device)
+        self.trans = to(trans, np.int32)
+        self.completes = to(np.asarray(completes).view(np.int64) if isinstance(completes, np.ndarray) else completes, np.int64)
+        self.scanner_of_state = to(scanner_of_state, np.int32)
+        self.shift = to(shift, np.int32)
+        self.n_states, self.n_classes = int(self.trans.shape[0]), int(self.trans.shape[1])
+        self.n_parse_states, self.n_terminals = int(self.shift.shape[0]), int(self.shift.shape[1])
+        self.dead_state = int(dead_state)
+        need = c_size_t()
+        _check(load().fsmidx_scanner_workspace_bytes(self.n_states, self.n_classes, byref(need)))
+        self.ws_bytes = int(need.value)
+        self._ws, self.ws_ptr = _aligned(self.ws_bytes, self.device)
+        self.c_dfa = CDfa(self.trans.data_ptr(), self.n_states, self.n_classes, None, None, self.dead_state)
+
+    def terminal_sets(self, out=None, stream=None):
+        """Returns (possible int64 [Q] on the device: the uint64 masks' bit patterns, launches)."""
+        import torch
+        if out is None:
+            out = torch.empty(self.n_states, dtype=torch.int64, device=self.device)
+        launches = c_int32()
+        _check(load().fsmidx_scanner_terminal_sets(byref(self.c_dfa), self.completes.data_ptr(), self.ws_ptr,
+                                                   self.ws_bytes, out.data_ptr(), byref(launches),
+                                                   _stream_handle(stream)))
+        return out, int(launches.value)
+
+    def restart_table(self, out=None, stream=None):
+        """Returns trans_out int32 [Q, C] on the device."""
+        import torch
+        if out is None:
+            out = torch.empty((self.n_states, self.n_classes), dtype=torch.int32, device=self.device)
+        _check(load().fsmidx_scanner_restart_table(byref(self.c_dfa), self.completes.data_ptr(),
+                                                   self.scanner_of_state.data_ptr(), self.shift.data_ptr(),
+                                                   self.n_parse_states, self.n_terminals, self.ws_ptr, self.ws_bytes,
+                                                   out.data_ptr(), _stream_handle(stream)))
+        return out
 
 
 def dedupe_rows(csr: CCsr, device="cuda:0", stream=None):

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libfsmidx.so")
 SOURCES = ["api.hip", "prepare.hip", "prepare_sets.hip", "walk.hip", "walk_sets.hip", "scan.hip", "emit.hip", "mask.hip", "decode.hip",
-           "argmax_static.hip", "reduce.hip", "reach.hip", "minimise.hip"]
+           "argmax_static.hip", "reduce.hip", "reach.hip", "minimise.hip", "scanner.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-parameter"]

@@ -139,6 +139,9 @@ static const char *flag_text(uint32_t flags)
     if (flags & kBadClass) return "a byte_to_class value is >= n_classes";
     if (flags & kBadOffsets) return "offsets are not 0 = o[0] <= o[1] <= ... <= o[n_tokens] = n_bytes";
     if (flags & kDeadNotAbsorbing) return "the dead state has a transition that leaves it";
+    if (flags & 32u) return "scanner_of_state lies outside [0, n_parse_states) for a state that completes a terminal";
+    if (flags & 64u) return "a shift value lies outside [-1, n_states)";
+    if (flags & 128u) return "completes has a bit at or above n_terminals";
     return "unknown";
 }
 
@@ -927,6 +930,108 @@ int fsmidx_dedupe_fill(const fsmidx_csr *index, const void *workspace, size_t wo
         return fail(FSMIDX_INVALID_ARG, "token_ids_out and next_states_out must not be NULL when the index has entries");
     FSMIDX_HIP(launch_dedupe_copy(*index, const_cast<char *>(static_cast<const char *>(workspace)), unique_row_ptr_dev,
                                   token_ids_out_dev, next_states_out_dev, static_cast<hipStream_t>(stream_v)));
+    return FSMIDX_OK;
+}
+
+static int check_scanner(const fsmidx_dfa *dfa, const uint64_t *completes_dev, void *workspace, size_t workspace_bytes)
+{
+    if (!dfa)
+        return fail(FSMIDX_INVALID_ARG, "scanner must not be NULL");
+    if (int rc = check_sizes(dfa->n_states, dfa->n_classes, 0, 0))
+        return rc;
+    if (!dfa->trans)
+        return fail(FSMIDX_INVALID_ARG, "scanner.trans must not be NULL");
+    if (dfa->dead_state < -1 || dfa->dead_state >= dfa->n_states)
+        return fail(FSMIDX_INVALID_ARG, "dead_state must be -1 or in [0, n_states) (got %d)", dfa->dead_state);
+    if (!completes_dev)
+        return fail(FSMIDX_INVALID_ARG, "completes must not be NULL");
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return fail(FSMIDX_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+    const size_t need = scanner_workspace_bytes(dfa->n_states, dfa->n_classes);
+    if (workspace_bytes < need)
+        return fail(FSMIDX_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    return FSMIDX_OK;
+}
+
+int fsmidx_scanner_workspace_bytes(int32_t n_states, int32_t n_classes, size_t *bytes)
+{
+    if (!bytes)
+        return fail(FSMIDX_INVALID_ARG, "bytes must not be NULL");
+    if (int rc = check_sizes(n_states, n_classes, 0, 0))
+        return rc;
+    *bytes = scanner_workspace_bytes(n_states, n_classes);
+    return FSMIDX_OK;
+}
+
+int fsmidx_scanner_terminal_sets(const fsmidx_dfa *scanner, const uint64_t *completes_dev, void *workspace,
+                                 size_t workspace_bytes, uint64_t *possible_out_dev, int32_t *launches_host,
+                                 void *stream_v)
+{
+    if (int rc = check_scanner(scanner, completes_dev, workspace, workspace_bytes))
+        return rc;
+    if (!possible_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "possible_out must not be NULL");
+    if (static_cast<const void *>(possible_out_dev) == static_cast<const void *>(completes_dev))
+        return fail(FSMIDX_INVALID_ARG, "possible_out must not be the completes array");
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    FSMIDX_HIP(launch_scanner_start(*scanner, completes_dev, ws, possible_out_dev, stream));
+    // Launches are enqueued in batches (4, then twice as many each time, 64 at most); one that finds
+    // nothing to change makes those after it return at once, and tells the host that the sets are
+    // final.  Every launch before that one moves some terminal at least one state further back, so
+    // 64 n_states launches are always enough.
+    int batch = 4;
+    int64_t launched = 0;
+    uint32_t flags = 0;
+    for (;;) {
+        FSMIDX_HIP(launch_scanner_sweeps(*scanner, ws, possible_out_dev, batch, stream));
+        uint32_t changed[64];
+        FSMIDX_HIP(hipMemcpyAsync(changed, scanner_changed(ws), (size_t)batch * 4, hipMemcpyDeviceToHost, stream));
+        FSMIDX_HIP(hipMemcpyAsync(&flags, scanner_flags(ws), 4, hipMemcpyDeviceToHost, stream));
+        FSMIDX_HIP(hipStreamSynchronize(stream));
+        if (flags)
+            return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(flags), flags);
+        bool done = false;
+        for (int i = 0; i < batch && !done; ++i) {
+            ++launched;
+            done = changed[i] == 0;
+        }
+        if (done)
+            break;
+        if (launched > 64ll * scanner->n_states + 64)
+            return fail(FSMIDX_HIP_ERROR, "the terminal sets did not settle");
+        if (batch < scanner_launches_max())
+            batch *= 2;
+    }
+    if (launches_host)
+        *launches_host = (int32_t)(launched > 0x7FFFFFFF ? 0x7FFFFFFF : launched);
+    return FSMIDX_OK;
+}
+
+int fsmidx_scanner_restart_table(const fsmidx_dfa *scanner, const uint64_t *completes_dev,
+                                 const int32_t *scanner_of_state_dev, const int32_t *shift_dev, int32_t n_parse_states,
+                                 int32_t n_terminals, void *workspace, size_t workspace_bytes, int32_t *trans_out_dev,
+                                 void *stream_v)
+{
+    if (int rc = check_scanner(scanner, completes_dev, workspace, workspace_bytes))
+        return rc;
+    if (n_terminals < 1 || n_terminals > 64)
+        return fail(FSMIDX_INVALID_ARG, "n_terminals must be in [1, 64] (got %d)", n_terminals);
+    if (n_parse_states < 1 || (int64_t)n_parse_states * n_terminals > 0x7FFFFFFFll)
+        return fail(FSMIDX_INVALID_ARG, "n_parse_states must be at least 1 and n_parse_states x n_terminals below 2^31");
+    if (!scanner_of_state_dev || !shift_dev || !trans_out_dev)
+        return fail(FSMIDX_INVALID_ARG, "scanner_of_state, shift and trans_out must not be NULL");
+    if (trans_out_dev == scanner->trans)
+        return fail(FSMIDX_INVALID_ARG, "trans_out must not be the scanner's own table");
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char *ws = static_cast<char *>(workspace);
+    FSMIDX_HIP(launch_scanner_restarts(*scanner, completes_dev, scanner_of_state_dev, shift_dev, n_parse_states, n_terminals,
+                                       trans_out_dev, ws, stream));
+    uint32_t flags = 0;
+    FSMIDX_HIP(hipMemcpyAsync(&flags, scanner_flags(ws), 4, hipMemcpyDeviceToHost, stream));
+    FSMIDX_HIP(hipStreamSynchronize(stream));
+    if (flags)
+        return fail(FSMIDX_BAD_DEVICE_INPUT, "device input rejected: %s (flags 0x%x)", flag_text(flags), flags);
     return FSMIDX_OK;
 }
 

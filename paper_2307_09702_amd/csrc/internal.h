@@ -191,6 +191,18 @@ hipError_t launch_union_table(const fsmidx_dfa *dfas, int32_t n_dfas, const int3
                               hipStream_t stream);
 // identical rows; ws starts with int64 [3]: distinct rows, their entries, collision flag
 // minimisation of an automaton (minimise.hip)
+// scanner step of parser-guided generation (scanner.hip)
+size_t scanner_workspace_bytes(int32_t n_states, int32_t n_classes);
+uint32_t *scanner_flags(char *ws);
+uint32_t *scanner_changed(char *ws);
+int scanner_launches_max();
+hipError_t launch_scanner_start(const fsmidx_dfa &dfa, const uint64_t *completes, char *ws, uint64_t *V,
+                                hipStream_t stream);
+hipError_t launch_scanner_sweeps(const fsmidx_dfa &dfa, char *ws, uint64_t *V, int n, hipStream_t stream);
+hipError_t launch_scanner_restarts(const fsmidx_dfa &dfa, const uint64_t *completes, const int32_t *scanner_of_state,
+                                   const int32_t *shift, int32_t n_parse_states, int32_t n_terminals, int32_t *out,
+                                   char *ws, hipStream_t stream);
+
 size_t minimise_workspace_bytes(int32_t n_states);
 hipError_t launch_min_start(const fsmidx_dfa &dfa, char *ws, bool first_attempt, hipStream_t stream);
 hipError_t launch_min_rounds(const fsmidx_dfa &dfa, char *ws, uint64_t seed, uint32_t first_round, int n_rounds,

@@ -273,3 +273,37 @@ def test_later_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, None, 4096, 4096, 3, None) == B.INVALID_ARG
     assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, 4096, 4096, 4096, -1, None) == B.INVALID_ARG
     assert lib.fsmidx_restrict_fill(ctypes.byref(csr), 4096, 4096, None, 4096, 3, None) == B.INVALID_ARG
+
+
+def test_scanner_entry_points_reject_bad_arguments_before_any_launch(lib):
+    """fsmidx_scanner_*: sizes, pointers, aliasing and the workspace are checked on the host."""
+    g = good()
+    d, _ = B._structs(g["trans"], g["byte_to_class"], g["accept"], 4, g["vocab_bytes"], g["offsets"], -1)
+    size = ctypes.c_size_t()
+    assert lib.fsmidx_scanner_workspace_bytes(5, 3, ctypes.byref(size)) == B.OK
+    assert size.value % 256 == 0 and size.value >= 512 + 5 * 3 * 4
+    assert lib.fsmidx_scanner_workspace_bytes(0, 3, ctypes.byref(size)) == B.INVALID_ARG
+    assert lib.fsmidx_scanner_workspace_bytes(5, 257, ctypes.byref(size)) == B.INVALID_ARG
+    assert lib.fsmidx_scanner_workspace_bytes(5, 3, None) == B.INVALID_ARG
+    lib.fsmidx_scanner_workspace_bytes(5, 3, ctypes.byref(size))
+    sets = lambda dfa, comp, ws, ws_bytes, out: lib.fsmidx_scanner_terminal_sets(dfa, comp, ws, ws_bytes, out, None, None)
+    assert sets(None, 4096, 4096, size.value, 8192) == B.INVALID_ARG
+    assert sets(ctypes.byref(d), None, 4096, size.value, 8192) == B.INVALID_ARG
+    assert sets(ctypes.byref(d), 4096, 4096 + 8, size.value, 8192) == B.INVALID_ARG
+    assert sets(ctypes.byref(d), 4096, 4096, size.value - 1, 8192) == B.WORKSPACE_TOO_SMALL
+    assert sets(ctypes.byref(d), 4096, 4096, size.value, None) == B.INVALID_ARG
+    assert sets(ctypes.byref(d), 4096, 4096, size.value, 4096) == B.INVALID_ARG          # out is the completes array
+    bad = B.CDfa(d.trans, d.n_states, d.n_classes, d.byte_to_class, d.accept, 5)
+    assert sets(ctypes.byref(bad), 4096, 4096, size.value, 8192) == B.INVALID_ARG
+    table = lambda dfa, comp, owner, shift, n_p, n_t, ws, ws_bytes, out: lib.fsmidx_scanner_restart_table(
+        dfa, comp, owner, shift, n_p, n_t, ws, ws_bytes, out, None)
+    ok = (ctypes.byref(d), 4096, 4096, 4096)
+    assert table(*ok, 2, 0, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(*ok, 2, 65, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(*ok, 0, 3, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(*ok, 2 ** 30, 64, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(ctypes.byref(d), 4096, None, 4096, 2, 3, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(ctypes.byref(d), 4096, 4096, None, 2, 3, 4096, size.value, 8192) == B.INVALID_ARG
+    assert table(*ok, 2, 3, 4096, size.value, None) == B.INVALID_ARG
+    assert table(*ok, 2, 3, 4096, size.value, ctypes.c_void_p(d.trans)) == B.INVALID_ARG                   # in place
+    assert table(*ok, 2, 3, 4096, size.value - 1, 8192) == B.WORKSPACE_TOO_SMALL
