@@ -152,6 +152,67 @@ def big_config_block(B, W, torch, dev, with_oracle):
     return out
 
 
+def scanner_block(B, W, torch, dev, with_oracle):
+    """Scanner step of parser-guided generation (Section 4, 4.1) on a seeded toy grammar: terminal
+    sets and the restart table for 2,000 parse states, and the index of 400 parse states' scanners,
+    with and without restarts, against the large vocabulary."""
+    import numpy as np
+    from paper_2307_09702_amd.synth import grammar as G
+
+    def timed(fn, n=5):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            out = fn()
+        torch.cuda.synchronize()
+        return out, (time.perf_counter() - t0) / n * 1e3
+
+    sc = G.toy_grammar(W.rng_for(12, 0), 2000)
+    d = sc.dfa
+    dev_sc = B.DeviceScanner(d.trans, d.dead, sc.completes, sc.scanner_of_state, sc.shift)
+    (sets, launches), sets_ms = timed(dev_sc.terminal_sets)
+    table, table_ms = timed(dev_sc.restart_table)
+    entries = d.n_states * d.n_classes
+    out = {"grammar": "seeded toy grammar: %d terminals, every parse state reads whitespace and 3 to 12 others; shifts drawn "
+                      "uniformly" % sc.n_terminals,
+           "kernels": {"parse_states": 2000, "states": d.n_states, "classes": d.n_classes,
+                       "terminal_sets_call_ms_host_clock": sets_ms, "terminal_sets_launches": launches,
+                       "restart_table_call_ms_host_clock": table_ms,
+                       "restart_table_bytes": entries * 8, "entries_rejecting_before": int((d.trans == d.dead).sum())}}
+    if with_oracle:
+        from oracle import scanner as S
+        t0 = time.perf_counter()
+        want_v = S.terminal_sets(d.trans, sc.completes)
+        want_t = S.restart_table(d.trans, d.dead, sc.completes, sc.scanner_of_state, sc.shift)
+        oracle_s = time.perf_counter() - t0
+        assert np.array_equal(sets.cpu().numpy().view(np.uint64), want_v), "terminal sets differ from the oracle"
+        assert np.array_equal(table.cpu().numpy(), want_t), "restart table differs from the oracle"
+        out["kernels"].update({"bit_exact_vs_oracle": True, "cpu_oracle_seconds": oracle_s,
+                               "entries_restarted": int((want_t != d.trans).sum())})
+    del dev_sc, sets, table
+    sc = G.toy_grammar(W.rng_for(12, 1), 400)
+    d = sc.dfa
+    vocab = W.large_vocab()
+    dev_sc = B.DeviceScanner(d.trans, d.dead, sc.completes, sc.scanner_of_state, sc.shift)
+    table = dev_sc.restart_table()
+    b2c = torch.from_numpy(d.byte_to_class).to(dev)
+    acc = torch.from_numpy(d.accept).to(dev)
+    built = {}
+    for name, trans in (("scanners_as_given", dev_sc.trans), ("with_restarts", table)):
+        prob = B.DeviceProblem(trans, b2c, acc, d.dead, vocab.bytes, vocab.offsets, -1)
+        nnz = prob.count()
+        tok = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+        nxt = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+        _, ms = timed(lambda: prob.build_into(tok, nxt), n=10)
+        built[name] = {"nnz": nnz, "build_ms": ms, "pairs_per_s": d.n_states * vocab.n_tokens / (ms * 1e-3)}
+        del prob, tok, nxt
+    out["index"] = {"parse_states": 400, "states": d.n_states, "classes": d.n_classes, "vocabulary": vocab.n_tokens,
+                    "pairs": d.n_states * vocab.n_tokens, **built}
+    torch.cuda.empty_cache()
+    return out
+
+
 def reduce_block(B, W, torch, dev, csr_large, n_states_large, nnz_large):
     """Index size (Section 5): eight schema automata in one build against one vocabulary, and
     identical rows kept once."""
@@ -429,6 +490,7 @@ def main():
     oop_bytes = {e: batch * n_vocab * e + kept * e + batch * n_vocab // 8 for e in (4, 2)}
     big = None if args.step_only else big_config_block(B, W, torch, dev, with_oracle=ref is not None)
     reduced = None if args.step_only else reduce_block(B, W, torch, dev, csr, d.n_states, nnz)
+    scanned = None if args.step_only else scanner_block(B, W, torch, dev, with_oracle=ref is not None)
 
     # The two heavy kernels of the build and what bounds each:
     #  - the counting walk decides all pairs: transition lookups of the early-exit walk (W_bf, from
@@ -484,6 +546,7 @@ def main():
                           "half the LDS-bound walk rate for the build as a whole is not met"},
         "configs": {"C4b-big": big},
         "index_size": reduced,
+        "parser_scanner": scanned,
         "mask": {
             "mode": "in place, 4 rotating buffers per dtype",
             "algorithmic_bytes": "removed entries x element size + one bitmap bit per element",

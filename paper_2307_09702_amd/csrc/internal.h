@@ -26,7 +26,7 @@ constexpr int kPackedClasses = 8;      // leading byte classes of a token packed
 
 // Token-set path (automata with <= 64 classes and few distinct targets per state).
 constexpr int kMaxSetDepth = 32;       // longest token (bytes) the path handles
-constexpr int kSetCap = 128;           // distinct class sets (one bitmap family each)
+constexpr int kSetCap = 256;           // distinct class sets (one bitmap family each)
 // most token blocks: the bitmaps U[kMaxSetDepth][kSetCap][64 per block] of 8-byte words stay below 4 GB
 constexpr int kMaxSetBlocks = 2047;
 constexpr int kSetHashSlots = 512;
