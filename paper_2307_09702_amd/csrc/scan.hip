@@ -60,6 +60,10 @@ __global__ __launch_bounds__(256) void scan_groups(uint32_t *__restrict__ cnt, i
 }
 
 // Also zeroes the work counters of the emit kernel that follows (token-set path: queue != NULL).
+// A thread takes kScanRows consecutive rows, so that a round of the workgroup covers 8192 rows: a
+// round costs three barriers and a trip to memory whatever it covers.
+constexpr int kScanRows = 8;
+
 __global__ __launch_bounds__(1024) void scan_rows(const int64_t *__restrict__ rowtot, int32_t n_states,
                                                   int64_t *__restrict__ row_ptr, uint32_t *__restrict__ queue,
                                                   Status *st)
@@ -73,21 +77,32 @@ __global__ __launch_bounds__(1024) void scan_rows(const int64_t *__restrict__ ro
     if (threadIdx.x == 0)
         carry_s = 0;
     __syncthreads();
-    for (int32_t q0 = 0; q0 < n_states; q0 += 1024) {
-        const int32_t q = q0 + (int32_t)threadIdx.x;
-        const int64_t v = q < n_states ? rowtot[q] : 0;
-        const int64_t incl = wave_inclusive_scan(v, lane);
+    for (int32_t q0 = 0; q0 < n_states; q0 += 1024 * kScanRows) {
+        const int32_t q = q0 + (int32_t)threadIdx.x * kScanRows;
+        int64_t v[kScanRows];
+#pragma unroll
+        for (int i = 0; i < kScanRows; ++i)
+            v[i] = q + i < n_states ? rowtot[q + i] : 0;
+        int64_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < kScanRows; ++i)
+            mine += v[i];
+        const int64_t incl = wave_inclusive_scan(mine, lane);
         if (lane == kWave - 1)
             wave_sum[wave] = incl;
         __syncthreads();
-        int64_t before = carry_s;
+        int64_t at = carry_s + incl - mine;
         for (int w = 0; w < wave; ++w)
-            before += wave_sum[w];
-        if (q < n_states)
-            row_ptr[q] = before + incl - v;
+            at += wave_sum[w];
+#pragma unroll
+        for (int i = 0; i < kScanRows; ++i) {
+            if (q + i < n_states)
+                row_ptr[q + i] = at;
+            at += v[i];
+        }
         __syncthreads();
         if (threadIdx.x == 1023)
-            carry_s = before + incl;
+            carry_s = at;
         __syncthreads();
     }
     if (threadIdx.x == 0) {
