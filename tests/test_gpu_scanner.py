@@ -152,3 +152,30 @@ def test_bad_device_inputs_are_reported_not_dereferenced(torch_mod):
     assert e.value.code == B.BAD_DEVICE_INPUT and "n_terminals" in str(e.value)
     # and the good inputs still go through afterwards
     check_both(torch_mod, sc)
+
+
+def test_benchmark_sizes_match_the_oracle(torch_mod, oracle_mod):
+    """The sizes the benchmark times: terminal sets and restart table of 2,000 parse states
+    (41,670 states), and the index of 400 parse states' automaton with restarts against the
+    128,256-token vocabulary (1.04 G pairs, 183 M entries), element by element."""
+    torch = torch_mod
+    check_both(torch, G.toy_grammar(W.rng_for(12, 0), 2000))
+    sc = G.toy_grammar(W.rng_for(12, 1), 400)
+    d = sc.dfa
+    vocab = W.large_vocab()
+    table = device_scanner(sc).restart_table()
+    on_device = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    prob = B.DeviceProblem(table, on_device(d.byte_to_class), on_device(d.accept), d.dead, vocab.bytes, vocab.offsets, -1)
+    nnz = prob.count()
+    tok = torch.empty(nnz, dtype=torch.int32, device="cuda")
+    nxt = torch.empty(nnz, dtype=torch.int32, device="cuda")
+    prob.build_into(tok, nxt)
+    torch.cuda.synchronize()
+    want_table = S.restart_table(d.trans, d.dead, sc.completes, sc.scanner_of_state, sc.shift)
+    want = oracle_mod.build_index(want_table, d.byte_to_class, d.accept, d.dead, vocab.bytes, vocab.offsets, -1)
+    assert nnz == want.token_ids.size
+    assert np.array_equal(prob.row_ptr.cpu().numpy(), want.row_ptr)
+    step = 1 << 25
+    for a in range(0, nnz, step):
+        assert np.array_equal(tok[a:a + step].cpu().numpy(), want.token_ids[a:a + step])
+        assert np.array_equal(nxt[a:a + step].cpu().numpy(), want.next_states[a:a + step])
