@@ -14,9 +14,10 @@ of place, with a plain fill of the same size as the ceiling; the decode-step cal
 the 20,000-state random automaton of the last config; the index-size calls (a union of eight
 schema automata built at once, identical rows kept once).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--workload C3|C4b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--workload C3|C4b|scanner]
 
-``--workload C4b`` is for profilers: its step is the build of the 20,000-state automaton alone.
+``--workload C4b`` is for profilers: its step is the build of the 20,000-state automaton alone;
+``--workload scanner`` likewise runs the parser extension's scanner calls and the two index builds that go with them.
 """
 from __future__ import annotations
 
@@ -321,8 +322,9 @@ def main():
     ap.add_argument("--step-only", action="store_true",
                     help="for profilers: leave out what is timed beside the step (other configs, index-size calls), so "
                          "that every kernel name in a trace belongs to the step's workload")
-    ap.add_argument("--workload", default="C3", choices=("C3", "C4b"),
-                    help="C4b: only the build of the 20,000-state automaton, for profilers")
+    ap.add_argument("--workload", default="C3", choices=("C3", "C4b", "scanner"),
+                    help="for profilers. C4b: only the build of the 20,000-state automaton; scanner: only the scanner "
+                         "step of the parser extension")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on exactly one GPU (one process, no collectives); "
@@ -344,6 +346,12 @@ def main():
         out = big_config_block(B, W, torch, dev, with_oracle=False)
         print(json.dumps({"metric": "(state,token) pairs indexed/sec", "value": out["pairs_per_s"], "unit": "pairs/s",
                           "n_gpus": 1, "config": out}))
+        return
+
+    if args.workload == "scanner":
+        out = scanner_block(B, W, torch, dev, with_oracle=False)
+        print(json.dumps({"metric": "(state,token) pairs indexed/sec", "value": out["index"]["with_restarts"]["pairs_per_s"],
+                          "unit": "pairs/s", "n_gpus": 1, "config": out}))
         return
 
     w = W.config_large()

@@ -145,11 +145,13 @@ __global__ __launch_bounds__(256) void scanner_restarts(const int32_t *__restric
                                                         const int32_t *__restrict__ shift, int32_t n_parse_states,
                                                         int32_t n_terminals, int32_t *__restrict__ out, ScannerHeader *h)
 {
-    const int64_t total = (int64_t)n_states * n_classes;
+    // (the table has fewer than 2^31 entries: 32-bit index arithmetic)
+    const uint32_t total = (uint32_t)n_states * (uint32_t)n_classes;
     const uint64_t known = n_terminals >= 64 ? ~0ull : (1ull << n_terminals) - 1ull;
     uint32_t bad = 0;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t q = (int32_t)(i / n_classes), c = (int32_t)(i - (int64_t)q * n_classes);
+    for (uint64_t at = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; at < total; at += (uint64_t)gridDim.x * blockDim.x) {
+        const uint32_t i = (uint32_t)at;
+        const int32_t q = (int32_t)(i / (uint32_t)n_classes), c = (int32_t)(i - (uint32_t)q * (uint32_t)n_classes);
         int32_t e = trans[i];
         if (e < 0 || e >= n_states) {
             bad |= kBadTransition;
