@@ -387,6 +387,35 @@ def test_more_distinct_class_sets_than_the_bitmap_table_holds(gpu, oracle_mod):
     assert_same_index(ref, row_ptr, tok, nxt, "many class sets")
 
 
+@pytest.mark.parametrize("n_live", [40, 63, 64, 65, 66, 100, 127, 128, 129, 130, 160])
+def test_numbers_of_distinct_class_sets_around_every_word_of_the_set_masks(gpu, oracle_mod, n_live):
+    # two targets per state, the 64 classes split differently in every state: about 2 n_live distinct
+    # sets, i.e. one to four 64-bit words of sets per class, and just past what the table holds
+    rng = np.random.default_rng(100 + n_live)
+    n_classes = 64
+    trans = np.empty((n_live + 1, n_classes), np.int32)
+    for s in range(n_live):
+        # (the other target reads nothing further, so that the search never has two ways to go on
+        # and stays within its stack whatever the tokens' lengths)
+        trans[s] = np.where(rng.random(n_classes) < 0.5, rng.integers(0, n_live - 1), n_live - 1)
+    trans[n_live - 1] = n_live
+    trans[n_live] = n_live
+    dfa = DFA(trans, W.random_partition(rng, n_classes), (rng.random(n_live + 1) < 0.3).astype(np.uint8), dead=n_live)
+    vocab = W.bpe_like_vocab(rng, 9000, 2.5, 10)
+    ref = oracle_index(oracle_mod, dfa, vocab, 5)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, 5)
+    assert_same_index(ref, row_ptr, tok, nxt, f"{n_live} states with two class sets each")
+
+
+def test_vocabulary_of_more_than_64_blocks_on_the_token_set_walk(gpu, oracle_mod):
+    # C2's automaton against 300,000 tokens: 74 blocks of 4096, more than a wave has lanes
+    w = W.CONFIGS[2]()
+    vocab = W.bpe_like_vocab(W.rng_for(2, 7), 300000, 4.0, 16)
+    ref = oracle_index(oracle_mod, w.dfa, vocab, 299999)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, w.dfa, vocab, 299999)
+    assert_same_index(ref, row_ptr, tok, nxt, "C2 x 300,000 tokens")
+
+
 def test_chain_automaton_with_eos_in_every_kind_of_block(gpu, oracle_mod):
     # C2 goes through the token-set walk; 50,257 tokens = 12 full blocks and a ragged one
     w = W.CONFIGS[2]()
