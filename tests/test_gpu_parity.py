@@ -629,6 +629,44 @@ def test_bad_device_inputs_are_reported_not_dereferenced(gpu):
     assert prob.count() > 0
 
 
+def many_three_way_states(n_live, seed):
+    """n_live states with three targets each -- a random state, and two states that read nothing
+    further -- over six fixed three-way splits of 48 classes: 3 pairs per state (the most the
+    token-set walk accepts on average), 18 distinct class sets, searches that never branch."""
+    rng = np.random.default_rng(seed)
+    n_classes = 48
+    # (the state that goes on has the widest class set: the search follows a node's last pair without
+    # a stack frame, so it never needs more than one whatever the tokens' lengths)
+    splits = [rng.permutation(np.repeat([0, 1, 2], [28, 10, 10])) for _ in range(6)]
+    end_a, end_b = n_live - 2, n_live - 1
+    trans = np.empty((n_live + 1, n_classes), np.int32)
+    nxt = rng.integers(0, n_live - 2, n_live)
+    which = rng.integers(0, 6, n_live)
+    for s in range(n_live):
+        trans[s] = np.choose(splits[which[s]], [nxt[s], end_a, end_b])
+    trans[end_a] = n_live
+    trans[end_b] = n_live
+    trans[n_live] = n_live
+    return DFA(trans, W.random_partition(rng, n_classes), (rng.random(n_live + 1) < 0.3).astype(np.uint8), dead=n_live)
+
+
+def test_twenty_thousand_states_with_three_targets_each(gpu, oracle_mod):
+    """More states with more than two pairs than the finishing workgroup's list holds at a time,
+    three rounds of 8192 states in it, and more workgroups of check words than it reads in one go."""
+    dfa = many_three_way_states(20000, 71)
+    vocab = W.bpe_like_vocab(np.random.default_rng(72), 5000, 3.0, 12)
+    ref = oracle_index(oracle_mod, dfa, vocab, 11)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, 11)
+    assert_same_index(ref, row_ptr, tok, nxt, "20,000 three-way states")
+    # a bad value in one of the last states is still found
+    bad = dfa.trans.copy()
+    bad[19990, 3] = 70000
+    prob = gpu.DeviceProblem(bad, dfa.byte_to_class, dfa.accept, dfa.dead, vocab.bytes, vocab.offsets, 11)
+    with pytest.raises(gpu.FsmidxError) as e:
+        prob.count()
+    assert e.value.code == gpu.BAD_DEVICE_INPUT and "transition" in str(e.value)
+
+
 # ----------------------------------------------------------------------------- mask_logits
 
 def without_bits(B, csr):
