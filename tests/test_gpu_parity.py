@@ -141,6 +141,28 @@ def test_empty_tokens_long_tokens_and_no_bytes(gpu, oracle_mod):
     assert_same_index(ref, row_ptr, tok, nxt, "no bytes")
 
 
+@pytest.mark.parametrize("n_live", [40, 9000])
+def test_tokens_around_the_widths_of_the_length_fields(gpu, oracle_mod, n_live):
+    """Runs of one byte that every state reads, 254 to 70,000 bytes long (lengths are kept in 8 bits
+    in the tokens' short form and in 16 bits in the dense walk's staging, with the record behind
+    both), among ordinary tokens; a small automaton and one large enough for the emit pass to take
+    the short form first."""
+    rng = np.random.default_rng(5 + n_live)
+    n_classes = 8
+    dfa = W.random_dfa(rng, n_live, n_classes, 0.5)
+    c = int(dfa.byte_to_class[ord("x")])
+    dfa.trans[:n_live, c] = rng.integers(0, n_live, n_live)         # "x" is read everywhere
+    runs = [b"x" * n for n in (254, 255, 256, 300, 65534, 65535, 65536, 70000)]
+    few = W.bpe_like_vocab(rng, 2000, 3.0, 12)
+    toks = [few.token(t) for t in range(1000)] + runs + [few.token(t) for t in range(1000, 2000)]
+    vocab = W.Vocab.from_tokens(toks)
+    ref = oracle_index(oracle_mod, dfa, vocab, 3)
+    _, _, row_ptr, tok, nxt = gpu_index_device_flow(gpu, dfa, vocab, 3)
+    assert_same_index(ref, row_ptr, tok, nxt, "very long tokens")
+    # every run is admissible from every live state
+    assert all(np.isin(np.arange(1000, 1008), ref.token_ids[ref.row_ptr[q]:ref.row_ptr[q + 1]]).all() for q in (0, n_live - 1))
+
+
 def test_no_dead_state_and_single_state(gpu, oracle_mod):
     rng = np.random.default_rng(8)
     trans = rng.integers(0, 7, size=(7, 3)).astype(np.int32)
