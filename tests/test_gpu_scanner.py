@@ -179,3 +179,21 @@ def test_benchmark_sizes_match_the_oracle(torch_mod, oracle_mod):
     for a in range(0, nnz, step):
         assert np.array_equal(tok[a:a + step].cpu().numpy(), want.token_ids[a:a + step])
         assert np.array_equal(nxt[a:a + step].cpu().numpy(), want.next_states[a:a + step])
+
+
+@pytest.mark.parametrize("n,n_classes", [(1, 1), (63, 64), (65, 65), (1037, 200), (4100, 256)])
+def test_random_tables_of_ragged_sizes(torch_mod, n, n_classes):
+    """Sizes that end inside a 64 x 64 tile of the transpose and inside a tile of 1,024 states, up to
+    256 byte classes; sparse random tables (long paths) with the last state rejecting."""
+    rng = W.rng_for(11, 100 + n)
+    trans = np.where(rng.random((n, n_classes)) < 2.0 / n_classes, rng.integers(0, n, size=(n, n_classes)), n - 1).astype(np.int32)
+    trans[n - 1] = n - 1
+    completes = np.zeros(n, dtype=np.uint64)
+    hit = rng.random(n) < 0.1
+    completes[hit] = rng.integers(1, 2 ** 20, size=int(hit.sum()), dtype=np.uint64)
+    completes[n - 1] = 0
+    owner = rng.integers(0, 3, size=n).astype(np.int32)
+    shift = rng.integers(-1, n, size=(3, 20)).astype(np.int32)
+    dev = B.DeviceScanner(trans, n - 1, completes, owner, shift)
+    assert np.array_equal(dev.terminal_sets()[0].cpu().numpy().view(np.uint64), S.terminal_sets(trans, completes))
+    assert np.array_equal(dev.restart_table().cpu().numpy(), S.restart_table(trans, n - 1, completes, owner, shift))
