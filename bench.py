@@ -322,6 +322,9 @@ def main():
     ap.add_argument("--step-only", action="store_true",
                     help="for profilers: leave out what is timed beside the step (other configs, index-size calls), so "
                          "that every kernel name in a trace belongs to the step's workload")
+    ap.add_argument("--in-flight", type=int, default=1, choices=(1, 2, 3, 4),
+                    help="steps under way at a time in the timed region, each on its own stream, workspace and output "
+                         "arrays (the default run also times two in flight, beside the headline)")
     ap.add_argument("--workload", default="C3", choices=("C3", "C4b", "scanner"),
                     help="for profilers. C4b: only the build of the 20,000-state automaton; scanner: only the scanner "
                          "step of the parser extension")
@@ -393,33 +396,77 @@ def main():
     kept = int(row_nnz.sum())
     batch, n_vocab = logits_np.shape
 
-    def step(i):
-        # the whole build enqueued at once (the arrays are known to be large enough from the first
-        # build), the two masks that use the index behind it on the same stream, and one wait at the
-        # end of the step: build_finish reads the build's status there and would say so if the
-        # counting pass had to be redone (then the masks would have to be enqueued again: not here)
-        prob.build_enqueue(token_ids, next_states)
-        B.mask_logits(csr, states, logits32[i % n_rot])
-        B.mask_logits(csr, states, logits16[i % n_rot])
-        got, redone = prob.build_finish(token_ids, next_states)
-        assert got == nnz and not redone
+    # A step: the whole build enqueued at once (the arrays are known to be large enough from the
+    # first build), the two masks that use the index behind it on the same stream, and one wait at
+    # the end of the step: build_finish reads the build's status there and would say so if the
+    # counting pass had to be redone (then the masks would have to be enqueued again: not here).
+    # Steps are independent of each other, so several can be under way at a time, each on a stream,
+    # a workspace and output arrays of its own: the preparation and the scans of one step are single
+    # workgroups waiting for memory, and run beside the emit pass and the masks of the step before,
+    # which fill the chip.  The headline is measured one step at a time (`--in-flight 1`, so that a
+    # kernel's duration is its own); two in flight are timed beside it.
+    class Slot:
+        def __init__(self, problem, tok, nxt, view):
+            self.prob, self.tok, self.nxt, self.csr = problem, tok, nxt, view
+            self.stream = torch.cuda.Stream()
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    # per-kernel durations from a second, untimed pass: the events that bracket the phases put
-    # gaps between the kernels, so they stay out of the timed steps
-    B.profile_enable(True)
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    prof = B.profile_read()
-    B.profile_enable(False)
+        def enqueue(self, i):
+            self.prob.build_enqueue(self.tok, self.nxt, stream=self.stream)
+            B.mask_logits(self.csr, states, logits32[i % n_rot], stream=self.stream)
+            B.mask_logits(self.csr, states, logits16[i % n_rot], stream=self.stream)
+
+        def finish(self):
+            got, redone = self.prob.build_finish(self.tok, self.nxt, stream=self.stream)
+            assert got == nnz and not redone
+
+    slots = [Slot(prob, token_ids, next_states, csr)]
+    most_in_flight = args.in_flight if args.step_only else max(args.in_flight, 2)
+    for _ in range(1, most_in_flight):
+        p2 = B.DeviceProblem(d.trans, d.byte_to_class, d.accept, d.dead, v.bytes, v.offsets, -1)
+        assert p2.count() == nnz
+        t2 = torch.empty(nnz, dtype=torch.int32, device=dev)
+        n2 = torch.empty(nnz, dtype=torch.int32, device=dev)
+        slots.append(Slot(p2, t2, n2, p2.csr(nnz, t2, n2)))
+
+    def run_steps(n_steps, in_flight):
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for i in range(n_steps):
+            slot = slots[i % in_flight]
+            if i >= in_flight:
+                slot.finish()
+            slot.enqueue(i)
+        for i in range(max(n_steps - in_flight, 0), n_steps):
+            slots[i % in_flight].finish()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_start
+
+    def profiled(in_flight):
+        # per-kernel durations from an untimed pass: the events that bracket the phases put gaps
+        # between the kernels, so they stay out of the timed steps
+        B.profile_enable(True)
+        run_steps(args.steps, in_flight)
+        out = B.profile_read()
+        B.profile_enable(False)
+        return out
+
+    run_steps(args.warmup, args.in_flight)
+    elapsed = run_steps(args.steps, args.in_flight)
+    prof = profiled(args.in_flight)
+    # the same steps with two under way, for comparison
+    piped = None
+    if most_in_flight > args.in_flight:
+        run_steps(min(args.warmup, 4), most_in_flight)
+        piped_elapsed = run_steps(args.steps, most_in_flight)
+        piped = {"steps_in_flight": most_in_flight, "ms_per_step": piped_elapsed / args.steps * 1e3,
+                 "value": n_pairs / (piped_elapsed / args.steps),
+                 "note": "the same steps, the next one enqueued on a second stream (own workspace and output arrays) "
+                         "before the one before it has been waited for; its preparation and scans run beside the "
+                         "other's emit pass and masks"}
+    if ref is not None and most_in_flight > 1:
+        for slot in slots[1:]:              # the other slots' indices are the same index
+            assert np.array_equal(slot.prob.row_ptr.cpu().numpy(), ref.row_ptr)
+            assert np.array_equal(slot.tok.cpu().numpy(), ref.token_ids) and np.array_equal(slot.nxt.cpu().numpy(), ref.next_states)
 
     # mask_logits on its own: 200 launches back to back per dtype over the rotating buffers, HIP
     # events on the launching stream around the lot (a decode step calls the mask without a build
@@ -538,10 +585,11 @@ def main():
                    "n_states": d.n_states, "n_classes": d.n_classes, "n_tokens": v.n_tokens,
                    "vocab_bytes": int(v.bytes.size), "pairs": n_pairs, "nnz": nnz,
                    "W_bf": ref.w_bf if ref else None, "W_inv": ref.w_inv if ref else None,
-                   "mask_batch": batch},
+                   "mask_batch": batch, "steps_in_flight": args.in_flight},
         "roofline": dominant,
         "roofline_second_kernel": other,
         "kernels_ms": ms,
+        "pipelined": piped,
         "build": {"ms": build_ms, "pairs_per_s": n_pairs / (build_ms * 1e-3),
                   "lookups_per_s": work / (build_ms * 1e-3),
                   "bytes_walked_per_s": work / (build_ms * 1e-3),
