@@ -501,6 +501,45 @@ def test_single_call_build_when_the_search_stack_overflows(gpu, oracle_mod):
     assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok.cpu().numpy(), nxt.cpu().numpy(), "overflow, single call")
 
 
+def test_two_builds_under_way_at_a_time_on_two_streams(gpu, oracle_mod):
+    """Two different problems, each with its own workspace, output arrays and stream, enqueued one
+    after the other and only then waited for, several times over (the token-set walk and the
+    lane-per-pair walk side by side; hints of earlier builds in use from the second time on)."""
+    import torch
+    cases = []
+    for cfg, eos in ((2, 50256), (1, 31999)):
+        w = W.CONFIGS[cfg]()
+        d, v = w.dfa, w.vocab
+        ref = oracle_index(oracle_mod, d, v, eos)
+        prob = gpu.DeviceProblem(d.trans, d.byte_to_class, d.accept, d.dead, v.bytes, v.offsets, eos)
+        tok = torch.empty(ref.nnz, dtype=torch.int32, device="cuda")
+        nxt = torch.empty(ref.nnz, dtype=torch.int32, device="cuda")
+        rng = np.random.default_rng(cfg)
+        states = rng.integers(-1, d.n_states, size=8).astype(np.int32)
+        logits = (rng.standard_normal((8, v.n_tokens)) * 3).astype(np.float32)
+        want = oracle_mod.mask_logits(ref, v.n_tokens, states, logits)
+        cases.append((prob, tok, nxt, ref, torch.cuda.Stream(), torch.from_numpy(states).cuda(), logits, want))
+    for repeat in range(4):
+        masked = []
+        for prob, tok, nxt, ref, stream, st, logits, want in cases:
+            tok.fill_(-7); nxt.fill_(-7)
+            torch.cuda.synchronize()
+        for prob, tok, nxt, ref, stream, st, logits, want in cases:
+            x = torch.from_numpy(logits).cuda()
+            torch.cuda.synchronize()
+            prob.build_enqueue(tok, nxt, stream=stream)
+            gpu.mask_logits(prob.csr(ref.nnz, tok, nxt), st, x, stream=stream)
+            masked.append(x)
+        for (prob, tok, nxt, ref, stream, st, logits, want), x in zip(cases, masked):
+            got, redone = prob.build_finish(tok, nxt, stream=stream)
+            assert got == ref.nnz
+            if redone:                                              # (first build without a hint may be redone: mask again)
+                gpu.mask_logits(prob.csr(ref.nnz, tok, nxt), st, x.copy_(torch.from_numpy(logits)), stream=stream)
+            stream.synchronize()
+            assert_same_index(ref, prob.row_ptr.cpu().numpy(), tok.cpu().numpy(), nxt.cpu().numpy(), f"repeat {repeat}")
+            assert x.cpu().numpy().tobytes() == want.tobytes()
+
+
 def test_build_in_two_halves_with_masks_enqueued_in_between(gpu, oracle_mod):
     """fsmidx_build_enqueue + fsmidx_build_finish: work enqueued between the two sees the finished
     index; a build whose counting pass has to be redone says so."""
