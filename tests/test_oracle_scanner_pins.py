@@ -175,3 +175,43 @@ def test_restart_table_properties_on_a_synthetic_grammar():
     # whitespace after a complete NAME is read by the parse state that follows the NAME
     v = S.terminal_sets(d.trans, sc.completes)
     assert int(v[d.dead]) == 0 and np.all((v & sc.completes) == sc.completes)
+
+
+def test_terminal_sets_of_a_union_are_the_components_own_futures():
+    """In the product of several terminal automata a state is a tuple of component states, and
+    terminal t is still possible there iff component t's own state can reach one of its final states:
+    a backward search in each component alone, never touching the union's table."""
+    from paper_2307_09702_amd.synth.regex_dfa import compile_regex as rx
+    parts = [rx("def"), W.name_dfa(), rx(r"[0-9]+(\.[0-9]+)?"), rx("de+f?"), rx(r"d\(")]
+    d, completes = G.tagged_union(parts)
+    v = S.terminal_sets(d.trans, completes)
+
+    def can_finish(a):
+        good = set(int(s) for s in np.flatnonzero(a.accept) if s != a.dead)
+        grew = True
+        while grew:
+            grew = False
+            for s in range(a.n_states):
+                if s not in good and s != a.dead and any(int(t) in good for t in a.trans[s]):
+                    good.add(s)
+                    grew = True
+        return good
+
+    futures = [can_finish(a) for a in parts]
+    # walk the union and every component side by side over all strings of up to 5 bytes of a small alphabet
+    alphabet = [ord(c) for c in "def0.(x"]
+    seen = 0
+    for length in range(6):
+        for word in itertools.product(alphabet, repeat=length):
+            q = 0
+            comp = [a.start for a in parts]
+            for byte in word:
+                q = int(d.trans[q, d.byte_to_class[byte]])
+                comp = [int(a.trans[s, a.byte_to_class[byte]]) for a, s in zip(parts, comp)]
+            want = sum(1 << t for t, (s, good) in enumerate(zip(comp, futures)) if s in good)
+            assert int(v[q]) == want, (bytes(word), int(v[q]), want)
+            seen += 1
+    assert seen > 10000
+    # every state's set holds what its successors' sets hold
+    for c in range(d.n_classes):
+        assert np.all((v & v[d.trans[:, c]]) == v[d.trans[:, c]])
