@@ -93,6 +93,7 @@ def python_like_scanners():
         row[0] = p
         row[ids[1]] = (p + 1) % len(reads)
         follows.append(row)
+    python_like_scanners.pieces = (automata, reads, follows)
     return G.scanner_layout(parts, follows, len(terms)), terms
 
 
@@ -215,3 +216,60 @@ def test_terminal_sets_of_a_union_are_the_components_own_futures():
     # every state's set holds what its successors' sets hold
     for c in range(d.n_classes):
         assert np.all((v & v[d.trans[:, c]]) == v[d.trans[:, c]])
+
+
+def test_restart_table_against_a_scanner_written_out_on_the_terminal_automata():
+    """The same lexing done the long way: a parse state, one state per terminal automaton it reads,
+    longest match, the terminals tried in list order when the current one ends -- on the component
+    automata, never on the laid-out table.  Random strings over the grammar's characters must be
+    rejected by both or end in the same parse state with the same terminals complete."""
+    sc, terms = python_like_scanners()
+    automata, reads, follows = python_like_scanners.pieces
+    d = sc.dfa
+    table = S.restart_table(d.trans, d.dead, sc.completes, sc.scanner_of_state, sc.shift)
+
+    def start(p, byte=None):
+        comp = {t: automata[t].start for t in reads[p]}
+        return comp if byte is None else advance(comp, byte)
+
+    def advance(comp, byte):
+        out = {}
+        for t, st in comp.items():
+            a = automata[t]
+            to = int(a.trans[st, a.byte_to_class[byte]])
+            if to != a.dead:
+                out[t] = to
+        return out
+
+    def lex(text):
+        p, comp = 0, start(0)
+        for byte in text:
+            nxt = advance(comp, byte)
+            if not nxt:
+                done = sorted((terms.index(t) for t, st in comp.items() if automata[t].accept[st]))
+                for t in done:
+                    p2 = follows[p][t]
+                    if p2 >= 0 and start(p2, byte):
+                        p, nxt = p2, start(p2, byte)
+                        break
+                if not nxt:
+                    return None
+            comp = nxt
+        return p, {t for t, st in comp.items() if automata[t].accept[st]}
+
+    rng = np.random.Generator(np.random.PCG64(44))
+    alphabet = np.frombuffer(b"defpas():x1 _", dtype=np.uint8)
+    accepted = 0
+    for _ in range(6000):
+        text = bytes(rng.choice(alphabet, size=int(rng.integers(1, 10))))
+        text = (b"def " if rng.random() < 0.5 else b"") + text
+        q = int(sc.start_of_scanner[0])
+        for byte in text:
+            q = int(table[q, d.byte_to_class[byte]])
+        want = lex(text)
+        if want is None:
+            assert q == d.dead, text
+        else:
+            accepted += 1
+            assert q != d.dead and int(sc.scanner_of_state[q]) == want[0] and names(sc.completes[q], terms) == want[1], text
+    assert accepted > 300
